@@ -1,0 +1,15 @@
+"""Seeded synthetic inputs for the QuoKA chunk-attention path.
+
+This package only *draws data*: random tensors with the shapes and geometry of
+the workloads, rounded to the storage dtype.  It holds none of the method's
+arithmetic (no query ranking, no key scoring, no attention) and is the one
+module both the CPU oracle's tests and the HIP path's tests/bench may share.
+"""
+from .workloads import (  # noqa: F401
+    Workload,
+    bf16_round,
+    bf16_bits,
+    make_workload,
+    make_custom,
+    CONFIG_NAMES,
+)

@@ -1,0 +1,127 @@
+"""Pins for the oracle's key scoring and top-B selection (Alg. 1 second block; Sec. 3.2-3.3)."""
+import numpy as np
+import pytest
+from scipy.spatial.distance import cdist
+
+import gen
+from oracle import quoka_oracle as O
+
+
+def _rand(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def test_group_of_one_is_max_of_library_cosines():
+    # n_q == n_kv: S-hat[t] = max_r cos(q_r, k_t), brute-forced with scipy's cosine distance.
+    Q = _rand(0, 2, 12, 6) + 0.4
+    K = _rand(1, 2, 30, 6)
+    q_idx = O.select_queries(Q, 5)
+    S = O.key_scores(Q, q_idx, K, n_kv=2)
+    for kv in range(2):
+        cosm = 1.0 - cdist(Q[kv][q_idx[kv]], K[kv], metric="cosine")     # [5, 30]
+        for t in range(30):
+            assert S[kv, t] == pytest.approx(max(cosm[r, t] for r in range(5)), abs=1e-12)
+
+
+def test_preaggregation_identity_of_section_3_3():
+    # mean over the group of per-head cosines == (mean of unit queries) . (unit key)
+    Q = _rand(2, 8, 20, 16) + 0.3
+    K = _rand(3, 2, 50, 16)
+    q_idx = O.select_queries(Q, 6)
+    post = O.key_scores(Q, q_idx, K, n_kv=2)
+    qbar = O.group_mean_queries(Q, q_idx, n_kv=2)
+    pre = O.key_scores_preagg(qbar, K)
+    assert qbar.shape == (2, 6, 16)
+    assert np.max(np.abs(post - pre)) < 1e-12
+
+
+def test_group_mean_pairs_queries_by_rank_and_uses_contiguous_groups():
+    # 4 q-heads, 2 KV heads: head h belongs to KV head h // 2; row r averages the r-th RANKED query of each head.
+    Q = _rand(4, 4, 9, 5) + 0.2
+    q_idx = O.select_queries(Q, 3)
+    qbar = O.group_mean_queries(Q, q_idx, n_kv=2)
+    for kv in range(2):
+        for r in range(3):
+            a = Q[2 * kv, q_idx[2 * kv, r]]
+            b = Q[2 * kv + 1, q_idx[2 * kv + 1, r]]
+            want = 0.5 * (a / np.linalg.norm(a) + b / np.linalg.norm(b))
+            assert np.allclose(qbar[kv, r], want, atol=1e-14)
+
+
+def test_scores_bounded_and_invariant_to_key_and_query_scale():
+    Q = _rand(5, 4, 16, 8) + 0.5
+    K = _rand(6, 2, 40, 8)
+    q_idx = O.select_queries(Q, 4)
+    S = O.key_scores(Q, q_idx, K, 2)
+    assert np.all(np.abs(S) <= 1.0 + 1e-12)
+    scale = np.random.default_rng(7).uniform(0.1, 9.0, size=(2, 40, 1))
+    assert np.allclose(O.key_scores(Q, q_idx, K * scale, 2), S, atol=1e-12)
+    # per-query positive rescaling does not change any cosine (same retained set passed in)
+    qs = np.random.default_rng(8).uniform(0.2, 5.0, size=(4, 16, 1))
+    assert np.allclose(O.key_scores(Q * qs, q_idx, K, 2), S, atol=1e-12)
+
+
+def test_max_not_mean_over_queries():
+    # One retained query is exactly parallel to key 3; every other (query, key) pair is orthogonal.
+    d = 8
+    Q = np.zeros((1, 3, d))
+    Q[0, 0, 0] = 1.0
+    Q[0, 1, 1] = 2.0
+    Q[0, 2, 2] = 0.5
+    K = np.zeros((1, 5, d))
+    K[0, :, 7] = 1.0           # orthogonal to all queries
+    K[0, 3] = 0.0
+    K[0, 3, 1] = 4.0           # parallel to query 1
+    S = O.key_scores(Q, np.array([[0, 1, 2]]), K, 1)
+    assert S[0].tolist() == [0.0, 0.0, 0.0, 1.0, 0.0]
+
+
+def test_zero_key_scores_zero():
+    Q = _rand(9, 1, 4, 4)
+    K = _rand(10, 1, 3, 4)
+    K[0, 1] = 0.0
+    S = O.key_scores(Q, O.select_queries(Q, 4), K, 1)
+    assert S[0, 1] == 0.0
+
+
+def test_topk_equals_exhaustive_sort():
+    s = _rand(11, 3, 200)
+    idx = O.topk_keys(s, 17)
+    assert idx.shape == (3, 17)
+    for kv in range(3):
+        ranked = sorted(range(200), key=lambda t: (-s[kv, t], t))
+        assert idx[kv].tolist() == sorted(ranked[:17])
+        assert np.all(np.diff(idx[kv]) > 0)
+        rest = set(range(200)) - set(idx[kv].tolist())
+        assert min(s[kv, t] for t in idx[kv]) >= max(s[kv, t] for t in rest)
+
+
+def test_topk_ties_lower_index_and_full_budget():
+    s = np.array([[1.0, 2.0, 2.0, 2.0, 0.5, 2.0]])
+    assert O.topk_keys(s, 2)[0].tolist() == [1, 2]
+    assert O.topk_keys(s, 4)[0].tolist() == [1, 2, 3, 5]
+    assert O.topk_keys(s, 6)[0].tolist() == [0, 1, 2, 3, 4, 5]
+    assert O.topk_keys(s, 99)[0].tolist() == [0, 1, 2, 3, 4, 5]
+    assert O.topk_keys(s, 0).shape == (1, 0)
+    assert O.topk_keys(np.zeros((2, 0)), 5).shape == (2, 0)
+
+
+def test_topk_is_equivariant_under_permutation_of_cache_positions():
+    r = np.random.default_rng(12)
+    s = r.standard_normal((1, 64))        # distinct scores almost surely
+    perm = r.permutation(64)
+    a = set(O.topk_keys(s, 9)[0].tolist())
+    b = set(O.topk_keys(s[:, perm], 9)[0].tolist())
+    assert {int(perm[j]) for j in b} == a
+
+
+def test_planted_heavy_keys_of_config1_are_selected():
+    w = gen.make_workload("c1")
+    q_idx, scores, k_idx = O.quoka_select(w.Q[0], w.K[0], w.n_retain, w.budgets[0])
+    assert k_idx.shape == (1, 128)
+    assert set(w.notes["heavy_key_pos"]) <= set(k_idx[0].tolist())
+    # each heavy key is parallel to one retained query of head 0 and the other head of the group is
+    # independent noise, so its group-mean score sits near 0.5 -- far above the bulk of the cache
+    heavy = scores[0, w.notes["heavy_key_pos"]]
+    assert np.all(heavy > 0.35)
+    assert np.quantile(scores[0], 0.99) < 0.35
