@@ -13,3 +13,13 @@ from .workloads import (  # noqa: F401
     make_custom,
     CONFIG_NAMES,
 )
+
+
+def to_torch(*a, **k):  # lazy: importing gen must not require torch
+    from .device import to_torch as f
+    return f(*a, **k)
+
+
+def from_torch(*a, **k):
+    from .device import from_torch as f
+    return f(*a, **k)

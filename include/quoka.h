@@ -1,0 +1,145 @@
+/*
+ * libquoka -- QuoKA's per-chunk sparse attention path for one AMD MI355X (gfx950).
+ *
+ * Method: "QuoKA: Query-oriented KV selection for efficient LLM prefill"
+ * (arXiv 2602.08722).  For one prefill chunk the library
+ *   1. keeps, per query head, the N_Q chunk queries with the lowest cosine similarity
+ *      to the chunk's mean query                         (Alg. 1, query sub-selection; Sec. 3.1),
+ *   2. scores every cached key by the maximum over retained queries of the group-averaged
+ *      query/key cosine                                   (Alg. 1, pre-aggregation; Sec. 3.2-3.3),
+ *   3. keeps the B_SA best keys per KV head               (Alg. 1, topk step; Eq. 3),
+ *   4. attends the chunk over [gathered keys | chunk keys] with a causal mask inside the chunk
+ *                                                         (Alg. 2, attention step; Eq. 2-3).
+ * A dense chunked-prefill attention (Eq. 2) is provided as the baseline.
+ *
+ * Conventions that hold for every entry point
+ *   - `shape` is a host pointer, read during the call, never retained.
+ *   - Every other pointer is a DEVICE pointer borrowed for the call; the caller owns all memory,
+ *     including the workspace.  The library never allocates, frees or keeps pointers.
+ *   - Tensors have head_dim contiguous; the three strides (batch, head, token) are in ELEMENTS and
+ *     must be multiples of 8 (16-byte rows for bf16); base pointers must be 16-byte aligned.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream).
+ *     No call synchronises the host: QUOKA_OK means "validated and enqueued".
+ *   - Argument problems are reported before anything is launched:
+ *       QUOKA_EINVAL       null pointer, non-positive size, n_q_heads % n_kv_heads != 0, bad stride
+ *       QUOKA_EUNSUPPORTED head_dim not in {64,128}, unknown dtype, size beyond a stated limit
+ *       QUOKA_EWORKSPACE   workspace smaller than quoka_workspace_bytes() says (or misaligned)
+ *       QUOKA_EHIP         the HIP runtime refused a launch
+ *   - Limits: n_retain <= 128, chunk_len <= 8192, max_kv_len < 2^24, max_budget <= max_kv_len.
+ *   - kv_lens[b] == 0 is legal (first chunk): nothing is selected and attention is plain causal
+ *     attention over the chunk.  A budget >= kv_lens[b] selects the whole cache.
+ *   - Inputs are assumed finite (no NaN/Inf).
+ *   - Calls are thread-safe for distinct streams with distinct workspaces and outputs.
+ */
+#ifndef QUOKA_H
+#define QUOKA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  QUOKA_OK = 0,
+  QUOKA_EINVAL = 1,
+  QUOKA_EUNSUPPORTED = 2,
+  QUOKA_EWORKSPACE = 3,
+  QUOKA_EHIP = 4
+} quoka_status;
+
+typedef enum { QUOKA_F32 = 0, QUOKA_BF16 = 1 } quoka_dtype;
+
+/* Problem description.  Notation of the paper: b, n_Q, n_KV, d, B_CP (chunk_len), T (kv length),
+ * N_Q (n_retain), B_SA (budget). */
+typedef struct quoka_shape {
+  int32_t batch;        /* b                                                                  */
+  int32_t n_q_heads;    /* n_Q; q-head h uses KV head h / (n_Q / n_KV)                        */
+  int32_t n_kv_heads;   /* n_KV                                                               */
+  int32_t head_dim;     /* d: 64 or 128                                                       */
+  int32_t chunk_len;    /* C = B_CP, the same for every sequence of the batch                 */
+  int32_t max_kv_len;   /* T_max: extent of the cache's token axis (may be 0)                 */
+  int32_t n_retain;     /* N_Q; N' = min(N_Q, C) queries are retained                         */
+  int32_t max_budget;   /* B_max: extent of k_idx's last axis                                 */
+  int32_t dtype;        /* quoka_dtype of Q, K, V, chunk K/V and O                            */
+  int32_t reserved;     /* must be 0                                                          */
+  int64_t q_stride[3];  /* Q        [b, n_Q,  C,     d]: batch, head, token strides (elements) */
+  int64_t kv_stride[3]; /* K, V     [b, n_KV, T_max, d] (K and V share strides)               */
+  int64_t ck_stride[3]; /* chunk KV [b, n_KV, C,     d] (chunk K and V share strides)         */
+  int64_t o_stride[3];  /* O        [b, n_Q,  C,     d]                                       */
+} quoka_shape;
+
+/* Bytes of device workspace that any entry point below may need for `shape`
+ * (one number covers all of them; the buffer must be 256-byte aligned). */
+quoka_status quoka_workspace_bytes(const quoka_shape* shape, size_t* out_bytes);
+
+/* Query sub-selection and pre-aggregation (Alg. 1: mean, CosSim, topk(-S_Q, N_Q), normalise,
+ * group mean; Sec. 3.1 and 3.3).
+ *   q      in   [b, n_Q, C, d] (shape.dtype)
+ *   q_idx  out  [b, n_Q, N'] int32: retained chunk positions per q-head, ordered by ascending
+ *               cosine to the head's mean query (ties: lower position first); 0..C-1 if C <= N_Q
+ *   qbar   out  [b, n_KV, N', d] float32, dense: row r = mean over the heads of the KV group of the
+ *               unit-normalised r-th retained query (norms clamped at 1e-8; not re-normalised)   */
+quoka_status quoka_select_queries(const quoka_shape* shape, const void* q, int32_t* q_idx, float* qbar,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Key scoring (Alg. 1: K normalisation, S = Qbar K^T, max over the query axis; Sec. 3.2-3.3).
+ *   qbar     in   [b, n_KV, N', d] float32 (as written by quoka_select_queries)
+ *   k_cache  in   [b, n_KV, T_max, d] (shape.dtype)
+ *   kv_lens  in   [b] int32, 0 <= kv_lens[b] <= T_max
+ *   scores   out  [b, n_KV, T_max] float32: scores[b,kv,t] = max_r <qbar[b,kv,r], K[b,kv,t]> /
+ *                 max(||K[b,kv,t]||, 1e-8) for t < kv_lens[b]; entries t >= kv_lens[b] unspecified.
+ * The product is accumulated in float32; for bf16 keys Qbar enters as an exact three-term bf16 split. */
+quoka_status quoka_score_keys(const quoka_shape* shape, const float* qbar, const void* k_cache,
+                              const int32_t* kv_lens, float* scores, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/* Key selection (Alg. 1: I = topk(S-hat, B_SA); Eq. 3).
+ *   scores   in   [b, n_KV, T_max] float32
+ *   kv_lens  in   [b] int32;  budgets in [b] int32 (B_SA per sequence, >= 0)
+ *   k_idx    out  [b, n_KV, B_max] int32: the k_cnt best positions, ASCENDING; equal scores go to the
+ *                 lower position; entries past k_cnt unspecified
+ *   k_cnt    out  [b, n_KV] int32 = min(budgets[b], kv_lens[b], B_max)                             */
+quoka_status quoka_topk_keys(const quoka_shape* shape, const float* scores, const int32_t* kv_lens,
+                             const int32_t* budgets, int32_t* k_idx, int32_t* k_cnt, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/* Chunk attention over the gathered cache rows and the chunk's own keys/values (Alg. 2 attention
+ * step; Eq. 2-3).  For q-head h (KV head kv), chunk position i:
+ *   O[b,h,i] = sum_j softmax_j(<Q[b,h,i], K_j> / sqrt(d)) V_j,
+ *   j over cache rows k_idx[b,kv,0..k_cnt[b,kv]) and chunk rows c <= i.
+ *   q, k_cache, v_cache, k_chunk, v_chunk  in (shape.dtype);  out [b, n_Q, C, d] (shape.dtype)
+ *   k_idx [b, n_KV, B_max], k_cnt [b, n_KV] as written by quoka_topk_keys (any order is accepted;
+ *   every index must be < T_max)
+ *   lse   out, optional (may be NULL) [b, n_Q, C] float32: natural-log softmax normaliser per row.
+ * bf16: QK^T and PV run on bf16 MFMA with float32 accumulation and float32 softmax state;
+ * f32: all arithmetic in float32.                                                                  */
+quoka_status quoka_sparse_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
+                               const int32_t* k_idx, const int32_t* k_cnt, const void* k_chunk,
+                               const void* v_chunk, void* out, float* lse, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/* Dense chunked-prefill attention, the baseline (Eq. 2): as quoka_sparse_attn with j over all cache
+ * rows t < kv_lens[b] and chunk rows c <= i. */
+quoka_status quoka_dense_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
+                              const int32_t* kv_lens, const void* k_chunk, const void* v_chunk, void* out,
+                              float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The four sparse stages back to back on one stream (Alg. 2, select-then-attend for one chunk).
+ * Intermediates are returned to the caller: q_idx, qbar, scores, k_idx, k_cnt as above. */
+quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
+                              const int32_t* kv_lens, const int32_t* budgets, const void* k_chunk,
+                              const void* v_chunk, int32_t* q_idx, float* qbar, float* scores, int32_t* k_idx,
+                              int32_t* k_cnt, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+const char* quoka_status_string(quoka_status status);
+
+/* major * 10000 + minor * 100 + patch */
+int quoka_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUOKA_H */

@@ -1,0 +1,217 @@
+// C-ABI layer of libquoka: argument validation, workspace carving, kernel dispatch.
+// Nothing here allocates, synchronises or keeps state.
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+#include "quoka.h"
+
+namespace {
+
+using quoka::Dims;
+
+constexpr int kMaxRetain = 128;
+constexpr int kMaxChunk = 8192;
+constexpr int kMaxKv = 1 << 24;
+constexpr size_t kAlign = 256;
+
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct WsLayout {
+  size_t select_off, select_bytes;
+  size_t topk_off, topk_bytes;
+  size_t total;
+};
+
+quoka_status check_shape(const quoka_shape* s, Dims* dm) {
+  if (s == nullptr) return QUOKA_EINVAL;
+  if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->chunk_len < 1 || s->n_retain < 1 ||
+      s->max_kv_len < 0 || s->max_budget < 0 || s->reserved != 0)
+    return QUOKA_EINVAL;
+  if (s->n_q_heads % s->n_kv_heads != 0) return QUOKA_EINVAL;
+  if (s->max_budget > s->max_kv_len) return QUOKA_EINVAL;
+  if (s->dtype != QUOKA_F32 && s->dtype != QUOKA_BF16) return QUOKA_EUNSUPPORTED;
+  if (s->head_dim != 64 && s->head_dim != 128) return QUOKA_EUNSUPPORTED;
+  if (s->n_retain > kMaxRetain || s->chunk_len > kMaxChunk || s->max_kv_len >= kMaxKv) return QUOKA_EUNSUPPORTED;
+  if ((long long)s->batch * s->n_q_heads > 65535 || s->batch > 65535) return QUOKA_EUNSUPPORTED;
+  const int64_t* strides[4] = {s->q_stride, s->kv_stride, s->ck_stride, s->o_stride};
+  for (const int64_t* st : strides) {
+    for (int i = 0; i < 3; ++i)
+      if (st[i] < 0 || st[i] % 8 != 0) return QUOKA_EINVAL;
+    if (st[2] < s->head_dim) return QUOKA_EINVAL;
+  }
+  dm->b = s->batch;
+  dm->n_q = s->n_q_heads;
+  dm->n_kv = s->n_kv_heads;
+  dm->g = s->n_q_heads / s->n_kv_heads;
+  dm->d = s->head_dim;
+  dm->C = s->chunk_len;
+  dm->T_max = s->max_kv_len;
+  dm->n_ret = s->n_retain;
+  dm->B_max = s->max_budget;
+  for (int i = 0; i < 3; ++i) {
+    dm->qs[i] = s->q_stride[i];
+    dm->kvs[i] = s->kv_stride[i];
+    dm->cks[i] = s->ck_stride[i];
+    dm->os[i] = s->o_stride[i];
+  }
+  return QUOKA_OK;
+}
+
+WsLayout layout(const Dims& dm) {
+  WsLayout l;
+  l.select_off = 0;
+  l.select_bytes = round_up(quoka::select_queries_ws_floats(dm) * sizeof(float), kAlign);
+  l.topk_off = l.select_off + l.select_bytes;
+  l.topk_bytes = round_up(quoka::topk_ws_words(dm) * sizeof(uint32_t), kAlign);
+  l.total = l.topk_off + l.topk_bytes;
+  if (l.total == 0) l.total = kAlign;
+  return l;
+}
+
+quoka_status check_ws(const WsLayout& l, const void* ws, size_t bytes) {
+  if (ws == nullptr) return QUOKA_EINVAL;
+  if (reinterpret_cast<uintptr_t>(ws) % kAlign != 0) return QUOKA_EWORKSPACE;
+  if (bytes < l.total) return QUOKA_EWORKSPACE;
+  return QUOKA_OK;
+}
+
+bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
+
+quoka_status from_hip(hipError_t e) { return e == hipSuccess ? QUOKA_OK : QUOKA_EHIP; }
+
+}  // namespace
+
+extern "C" {
+
+quoka_status quoka_workspace_bytes(const quoka_shape* shape, size_t* out_bytes) {
+  Dims dm;
+  quoka_status st = check_shape(shape, &dm);
+  if (st != QUOKA_OK) return st;
+  if (out_bytes == nullptr) return QUOKA_EINVAL;
+  *out_bytes = layout(dm).total;
+  return QUOKA_OK;
+}
+
+quoka_status quoka_select_queries(const quoka_shape* shape, const void* q, int32_t* q_idx, float* qbar,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  Dims dm;
+  quoka_status st = check_shape(shape, &dm);
+  if (st != QUOKA_OK) return st;
+  if (q == nullptr || q_idx == nullptr || qbar == nullptr) return QUOKA_EINVAL;
+  if (!aligned16(q) || !aligned16(qbar)) return QUOKA_EINVAL;
+  const WsLayout l = layout(dm);
+  st = check_ws(l, workspace, workspace_bytes);
+  if (st != QUOKA_OK) return st;
+  float* ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + l.select_off);
+  return from_hip(quoka::launch_select_queries(dm, shape->dtype, q, q_idx, qbar, ws, static_cast<hipStream_t>(stream)));
+}
+
+quoka_status quoka_score_keys(const quoka_shape* shape, const float* qbar, const void* k_cache,
+                              const int32_t* kv_lens, float* scores, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  Dims dm;
+  quoka_status st = check_shape(shape, &dm);
+  if (st != QUOKA_OK) return st;
+  if (qbar == nullptr || kv_lens == nullptr) return QUOKA_EINVAL;
+  if (dm.T_max > 0 && (k_cache == nullptr || scores == nullptr)) return QUOKA_EINVAL;
+  if (!aligned16(qbar) || !aligned16(k_cache)) return QUOKA_EINVAL;
+  st = check_ws(layout(dm), workspace, workspace_bytes);
+  if (st != QUOKA_OK) return st;
+  return from_hip(
+      quoka::launch_score_keys(dm, shape->dtype, qbar, k_cache, kv_lens, scores, static_cast<hipStream_t>(stream)));
+}
+
+quoka_status quoka_topk_keys(const quoka_shape* shape, const float* scores, const int32_t* kv_lens,
+                             const int32_t* budgets, int32_t* k_idx, int32_t* k_cnt, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  Dims dm;
+  quoka_status st = check_shape(shape, &dm);
+  if (st != QUOKA_OK) return st;
+  if (kv_lens == nullptr || budgets == nullptr || k_cnt == nullptr) return QUOKA_EINVAL;
+  if (dm.T_max > 0 && scores == nullptr) return QUOKA_EINVAL;
+  if (dm.B_max > 0 && k_idx == nullptr) return QUOKA_EINVAL;
+  const WsLayout l = layout(dm);
+  st = check_ws(l, workspace, workspace_bytes);
+  if (st != QUOKA_OK) return st;
+  uint32_t* ws = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + l.topk_off);
+  return from_hip(
+      quoka::launch_topk_keys(dm, scores, kv_lens, budgets, k_idx, k_cnt, ws, static_cast<hipStream_t>(stream)));
+}
+
+static quoka_status attn_common(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
+                                const int32_t* k_idx, const int32_t* n_cache, bool sparse, const void* k_chunk,
+                                const void* v_chunk, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  Dims dm;
+  quoka_status st = check_shape(shape, &dm);
+  if (st != QUOKA_OK) return st;
+  if (q == nullptr || k_chunk == nullptr || v_chunk == nullptr || out == nullptr || n_cache == nullptr)
+    return QUOKA_EINVAL;
+  const bool has_cache = sparse ? dm.B_max > 0 : dm.T_max > 0;
+  if (has_cache && (k_cache == nullptr || v_cache == nullptr)) return QUOKA_EINVAL;
+  if (sparse && dm.B_max > 0 && k_idx == nullptr) return QUOKA_EINVAL;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_chunk) || !aligned16(v_chunk) ||
+      !aligned16(out))
+    return QUOKA_EINVAL;
+  st = check_ws(layout(dm), workspace, workspace_bytes);
+  if (st != QUOKA_OK) return st;
+  quoka::AttnArgs a;
+  a.q = q;
+  a.k_cache = k_cache;
+  a.v_cache = v_cache;
+  a.k_chunk = k_chunk;
+  a.v_chunk = v_chunk;
+  // a null k_idx selects the dense kernel path, so a sparse call with B_max == 0 still needs a non-null marker:
+  // n_cache is then 0 everywhere and k_idx is never dereferenced.
+  a.k_idx = sparse ? (k_idx != nullptr ? k_idx : n_cache) : nullptr;
+  a.n_cache = n_cache;
+  a.out = out;
+  a.lse = lse;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  return from_hip(shape->dtype == QUOKA_BF16 ? quoka::launch_attn_bf16(dm, a, hs) : quoka::launch_attn_f32(dm, a, hs));
+}
+
+quoka_status quoka_sparse_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
+                               const int32_t* k_idx, const int32_t* k_cnt, const void* k_chunk,
+                               const void* v_chunk, void* out, float* lse, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  return attn_common(shape, q, k_cache, v_cache, k_idx, k_cnt, true, k_chunk, v_chunk, out, lse, workspace,
+                     workspace_bytes, stream);
+}
+
+quoka_status quoka_dense_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
+                              const int32_t* kv_lens, const void* k_chunk, const void* v_chunk, void* out,
+                              float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  return attn_common(shape, q, k_cache, v_cache, nullptr, kv_lens, false, k_chunk, v_chunk, out, lse, workspace,
+                     workspace_bytes, stream);
+}
+
+quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
+                              const int32_t* kv_lens, const int32_t* budgets, const void* k_chunk,
+                              const void* v_chunk, int32_t* q_idx, float* qbar, float* scores, int32_t* k_idx,
+                              int32_t* k_cnt, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  quoka_status st = quoka_select_queries(shape, q, q_idx, qbar, workspace, workspace_bytes, stream);
+  if (st != QUOKA_OK) return st;
+  st = quoka_score_keys(shape, qbar, k_cache, kv_lens, scores, workspace, workspace_bytes, stream);
+  if (st != QUOKA_OK) return st;
+  st = quoka_topk_keys(shape, scores, kv_lens, budgets, k_idx, k_cnt, workspace, workspace_bytes, stream);
+  if (st != QUOKA_OK) return st;
+  return quoka_sparse_attn(shape, q, k_cache, v_cache, k_idx, k_cnt, k_chunk, v_chunk, out, lse, workspace,
+                           workspace_bytes, stream);
+}
+
+const char* quoka_status_string(quoka_status status) {
+  switch (status) {
+    case QUOKA_OK: return "ok";
+    case QUOKA_EINVAL: return "invalid argument";
+    case QUOKA_EUNSUPPORTED: return "unsupported shape or dtype";
+    case QUOKA_EWORKSPACE: return "workspace too small or misaligned";
+    case QUOKA_EHIP: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+int quoka_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,284 @@
+// Chunk attention on bf16 MFMA (Alg. 2 attention step; Eq. 2-3): flash-style online softmax over
+// [gathered cache rows | chunk rows], causal inside the chunk.  One kernel serves the sparse path
+// (rows gathered through k_idx while the tile is staged into LDS -- the reduced cache of Eq. 3 is
+// never materialised) and the dense baseline of Eq. 2 (rows 0..kv_len).
+//
+// Work split: a wave owns 32 query rows of one q-head; the four waves of a block take four
+// consecutive (token tile, head-in-group) row blocks of one KV head, so with a group of 4 the block's
+// waves are the 4 q-heads that share every staged K/V tile.
+//
+// MFMA operand plan (v_mfma_f32_32x32x16_bf16; a lane is (li = lane % 32, hf = lane / 32)):
+//   S^T[key, row] = K[key, :] . Q[row, :]      A = K tile rows from LDS, B = Q held in registers.
+//     Result layout: lane li = query row, 16 registers = keys 8*(v/4) + 4*hf + v%4 of a 32-key block.
+//     Row max / row sum are therefore in-lane plus one exchange between the two half waves.
+//   O^T[dim, row] += V[key, dim] . P[row, key]  B = P: exactly the registers S^T left in the lane
+//     (the contraction index may be permuted freely, so no transpose or shuffle is needed),
+//     A = V read from the row-major LDS tile as DB consecutive dims per lane: lane li takes dims
+//     DB*li .. DB*li+DB-1 of 8 keys and feeds one element to each of the DB dim-blocks.
+//     Accumulator block c, register v of lane li holds O[row li, dim DB*(8*(v/4)+4*hf+v%4) + c].
+#include "common.hip.h"
+#include "kernels.h"
+
+namespace quoka {
+
+constexpr int kAtThreads = 256;
+constexpr int kBN = 64;   // keys per staged tile
+
+template <int D>
+struct AttnCfg {
+  static constexpr int KS = D / 16;              // k-steps of the QK^T product
+  static constexpr int LD = D + 8;               // padded LDS row (elements)
+  static constexpr int CG = D / 8;               // 16-byte chunks per row
+  static constexpr int RPI = kAtThreads / CG;    // rows per block-wide load
+  static constexpr int NLD = kBN / RPI;          // loads per thread per tile (per tensor)
+  static constexpr int DB = D / 32;              // dim blocks of the PV product
+  static constexpr size_t kTileBytes = (size_t)kBN * LD * 2;
+  static constexpr size_t kLdsBytes = 4 * kTileBytes;  // K and V, double buffered
+};
+
+template <int D>
+__global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) {
+  using Cfg = AttnCfg<D>;
+  constexpr int KS = Cfg::KS, LD = Cfg::LD, CG = Cfg::CG, RPI = Cfg::RPI, NLD = Cfg::NLD, DB = Cfg::DB;
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int kv = blockIdx.x, b = blockIdx.z;   // KV head fastest: one head's blocks share an XCD's L2
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int li = lane & 31, hf = lane >> 5;
+  const int C = dm.C, g = dm.g;
+  const int ntt = (C + 31) / 32;
+  const int nrb = g * ntt;                       // row blocks of this KV head
+  const int x = blockIdx.y * 4 + w;
+  const bool wave_on = x < nrb;
+  const int xj = wave_on ? x % g : 0;
+  const int tok0 = wave_on ? (x / g) * 32 : 0;
+  const int h = kv * g + xj;
+  const int x_hi = min((int)blockIdx.y * 4 + 3, nrb - 1);
+  const int c_end_blk = min((x_hi / g) * 32 + 32, C);   // chunk keys any wave of this block can see
+
+  const bool sparse = a.k_idx != nullptr;
+  int n_cache;
+  if (sparse) {
+    n_cache = min(a.n_cache[b * dm.n_kv + kv], dm.B_max);
+  } else {
+    n_cache = min(a.n_cache[b], dm.T_max);
+  }
+  n_cache = max(n_cache, 0);
+  const int n_ct = (n_cache + kBN - 1) / kBN;
+  const int n_tiles = n_ct + (c_end_blk + kBN - 1) / kBN;
+
+  const uint16_t* qg = static_cast<const uint16_t*>(a.q);
+  const uint16_t* kcache = static_cast<const uint16_t*>(a.k_cache) + b * dm.kvs[0] + kv * dm.kvs[1];
+  const uint16_t* vcache = static_cast<const uint16_t*>(a.v_cache) + b * dm.kvs[0] + kv * dm.kvs[1];
+  const uint16_t* kchunk = static_cast<const uint16_t*>(a.k_chunk) + b * dm.cks[0] + kv * dm.cks[1];
+  const uint16_t* vchunk = static_cast<const uint16_t*>(a.v_chunk) + b * dm.cks[0] + kv * dm.cks[1];
+  const int32_t* kidx = sparse ? a.k_idx + (size_t)(b * dm.n_kv + kv) * dm.B_max : nullptr;
+
+  // Q operand: row tok0 + li, dims ks*16 + 8*hf .. +8
+  bf16x8 qreg[KS];
+  {
+    const int tok = min(tok0 + li, C - 1);
+    const uint16_t* qrow = qg + b * dm.qs[0] + h * dm.qs[1] + (size_t)tok * dm.qs[2] + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
+  }
+
+  const int cg = tid % CG, r0 = tid / CG;
+  int rows[NLD];       // resolved source rows of the tile to be issued next
+  uint4 RK[NLD], RV[NLD];
+
+  auto resolve = [&](int it) {
+    if (it >= n_tiles) return;
+    if (it < n_ct) {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int n = min(it * kBN + r0 + RPI * i, n_cache - 1);   // tail slots repeat a real row (masked later)
+        rows[i] = sparse ? kidx[n] : n;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) rows[i] = min((it - n_ct) * kBN + r0 + RPI * i, C - 1);
+    }
+  };
+  auto issue = [&](int it) {
+    if (it < n_ct) {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const size_t off = (size_t)rows[i] * dm.kvs[2] + cg * 8;
+        RK[i] = *reinterpret_cast<const uint4*>(kcache + off);
+        RV[i] = *reinterpret_cast<const uint4*>(vcache + off);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const size_t off = (size_t)rows[i] * dm.cks[2] + cg * 8;
+        RK[i] = *reinterpret_cast<const uint4*>(kchunk + off);
+        RV[i] = *reinterpret_cast<const uint4*>(vchunk + off);
+      }
+    }
+  };
+
+  resolve(0);
+  issue(0);
+  resolve(1);
+
+  f32x16 o[DB];
+#pragma unroll
+  for (int c = 0; c < DB; ++c)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[c][v] = 0.f;
+  float m_run = -INFINITY;   // running row max, in the scaled log2 domain
+  float l_run = 0.f;         // this half wave's share of the running row sum
+  const float sl2 = 1.4426950408889634f / sqrtf((float)D);
+  const int tok = tok0 + li;
+
+  for (int it = 0; it < n_tiles; ++it) {
+    uint16_t* kt = reinterpret_cast<uint16_t*>(smem + (size_t)(it & 1) * 2 * Cfg::kTileBytes);
+    uint16_t* vt = kt + kBN * LD;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int rl = r0 + RPI * i;
+      *reinterpret_cast<uint4*>(kt + rl * LD + cg * 8) = RK[i];
+      *reinterpret_cast<uint4*>(vt + rl * LD + cg * 8) = RV[i];
+    }
+    __syncthreads();   // tile `it` visible; every wave is past its reads of the other buffer's previous use
+    if (it + 1 < n_tiles) {
+      issue(it + 1);
+      resolve(it + 2);
+    }
+
+    const bool is_chunk = it >= n_ct;
+    const int base = is_chunk ? (it - n_ct) * kBN : it * kBN;   // first key of the tile in its own numbering
+    if (!wave_on || (is_chunk && base > tok0 + 31)) continue;   // tile entirely in this wave's future
+
+    // ---- S^T = K Q^T --------------------------------------------------------------------------
+    f32x16 s[2];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
+      const uint16_t* kp = kt + (nb * 32 + li) * LD + 8 * hf;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 kop = *reinterpret_cast<const bf16x8*>(kp + ks * 16);
+        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[ks], s[nb], 0, 0, 0);
+      }
+    }
+    // ---- mask ---------------------------------------------------------------------------------
+    const int limit = is_chunk ? (tok - base + 1) : (n_cache - base);   // keys kk < limit are visible
+    if (limit < kBN) {   // lane-varying for chunk tiles; only comparisons, no cross-lane traffic inside
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int kk = nb * 32 + 8 * (v / 4) + 4 * hf + (v % 4);
+          if (kk >= limit) s[nb][v] = -INFINITY;
+        }
+    }
+    // ---- online softmax -----------------------------------------------------------------------
+    float mx = -INFINITY;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
+    mx = fmaxf(mx, other_half(mx));
+    const float m_new = fmaxf(m_run, mx * sl2);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[nb][v], sl2, -m_use));
+        s[nb][v] = p;
+        psum += p;
+      }
+    l_run = fmaf(l_run, alpha, psum);
+#pragma unroll
+    for (int c = 0; c < DB; ++c)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[c][v] *= alpha;
+    // ---- O^T += V^T P^T -----------------------------------------------------------------------
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)s[nb][8 * t + e];
+        // the 8 keys behind this lane's k-slots: 16t + 8*(e/4) + 4*hf + e%4 of block nb
+        uint16_t ve[8][DB];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int kk = nb * 32 + 16 * t + 8 * (e / 4) + 4 * hf + (e % 4);
+          const uint16_t* vp = vt + kk * LD + DB * li;
+          if constexpr (DB == 4) {
+            const uint2 r = *reinterpret_cast<const uint2*>(vp);
+            ve[e][0] = (uint16_t)(r.x & 0xFFFFu); ve[e][1] = (uint16_t)(r.x >> 16);
+            ve[e][2] = (uint16_t)(r.y & 0xFFFFu); ve[e][3] = (uint16_t)(r.y >> 16);
+          } else {
+            const uint32_t r = *reinterpret_cast<const uint32_t*>(vp);
+            ve[e][0] = (uint16_t)(r & 0xFFFFu); ve[e][1] = (uint16_t)(r >> 16);
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < DB; ++c) {
+          uint4 packed;
+          packed.x = (uint32_t)ve[0][c] | ((uint32_t)ve[1][c] << 16);
+          packed.y = (uint32_t)ve[2][c] | ((uint32_t)ve[3][c] << 16);
+          packed.z = (uint32_t)ve[4][c] | ((uint32_t)ve[5][c] << 16);
+          packed.w = (uint32_t)ve[6][c] | ((uint32_t)ve[7][c] << 16);
+          const bf16x8 vop = __builtin_bit_cast(bf16x8, packed);
+          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pb, o[c], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- epilogue -------------------------------------------------------------------------------
+  const float l_tot = l_run + other_half(l_run);
+  if (wave_on && tok < C) {
+    const float inv = 1.0f / l_tot;
+    uint16_t* orow = static_cast<uint16_t*>(a.out) + b * dm.os[0] + h * dm.os[1] + (size_t)tok * dm.os[2];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int iv = 8 * (v / 4) + 4 * hf + (v % 4);
+      if constexpr (DB == 4) {
+        uint2 pk;
+        pk.x = f32_to_bf16_bits(o[0][v] * inv) | (f32_to_bf16_bits(o[1][v] * inv) << 16);
+        pk.y = f32_to_bf16_bits(o[2][v] * inv) | (f32_to_bf16_bits(o[3][v] * inv) << 16);
+        *reinterpret_cast<uint2*>(orow + 4 * iv) = pk;
+      } else {
+        const uint32_t pk = f32_to_bf16_bits(o[0][v] * inv) | (f32_to_bf16_bits(o[1][v] * inv) << 16);
+        *reinterpret_cast<uint32_t*>(orow + 2 * iv) = pk;
+      }
+    }
+    if (a.lse != nullptr && hf == 0) {
+      a.lse[(size_t)(b * dm.n_q + h) * C + tok] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+    }
+  }
+}
+
+template <int D>
+static hipError_t launch_d(const Dims& dm, const AttnArgs& a, hipStream_t st) {
+  using Cfg = AttnCfg<D>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16<D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int nrb = dm.g * ((dm.C + 31) / 32);
+  dim3 grid(dm.n_kv, (nrb + 3) / 4, dm.b);
+  hipLaunchKernelGGL((attn_bf16<D>), grid, dim3(kAtThreads), Cfg::kLdsBytes, st, dm, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bf16(const Dims& dm, const AttnArgs& a, hipStream_t st) {
+  return dm.d == 64 ? launch_d<64>(dm, a, st) : launch_d<128>(dm, a, st);
+}
+
+}  // namespace quoka

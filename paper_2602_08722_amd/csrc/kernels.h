@@ -1,0 +1,37 @@
+// Internal launcher interface between the C-ABI layer (api.hip) and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "common.hip.h"
+
+namespace quoka {
+
+// --- query sub-selection (select_queries.hip) -------------------------------------------------
+size_t select_queries_ws_floats(const Dims& dm);
+hipError_t launch_select_queries(const Dims& dm, int dtype, const void* q, int32_t* q_idx, float* qbar, float* ws,
+                                 hipStream_t st);
+
+// --- key scoring (score_keys.hip) ---------------------------------------------------------------
+hipError_t launch_score_keys(const Dims& dm, int dtype, const float* qbar, const void* k_cache, const int32_t* kv_lens,
+                             float* scores, hipStream_t st);
+
+// --- top-B key selection (topk_keys.hip) ----------------------------------------------------------
+size_t topk_ws_words(const Dims& dm);
+hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* kv_lens, const int32_t* budgets,
+                            int32_t* k_idx, int32_t* k_cnt, uint32_t* ws, hipStream_t st);
+
+// --- attention (attn_mfma.hip for bf16, attn_f32.hip for float32) ---------------------------------
+// Cache rows attended: sparse (k_idx != nullptr): k_idx[b,kv,0..k_cnt[b,kv]); dense: 0..kv_lens[b].
+struct AttnArgs {
+  const void *q, *k_cache, *v_cache, *k_chunk, *v_chunk;
+  const int32_t* k_idx;    // nullptr for dense
+  const int32_t* n_cache;  // k_cnt [b,n_kv] (sparse) or kv_lens [b] (dense)
+  void* out;
+  float* lse;              // may be nullptr
+};
+hipError_t launch_attn_bf16(const Dims& dm, const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_f32(const Dims& dm, const AttnArgs& a, hipStream_t st);
+
+}  // namespace quoka

@@ -1,0 +1,254 @@
+// Query sub-selection and group pre-aggregation (Alg. 1, first block and the normalise / group-mean steps;
+// Sec. 3.1, 3.3).  Four small kernels:
+//   sq_partial_sums : per (b, q-head, token tile) column sums of Q                     -> ws.part
+//   sq_cosine       : per (b, q-head, token tile) mean query from the partials (fixed order, so the
+//                     result is bit-reproducible), then CosSim(q_i, M_Q) for the tile   -> ws.cos
+//   sq_select       : per (b, q-head) the N' lowest cosines in rank order (LDS radix select + rank
+//                     by counting)                                                      -> q_idx
+//   sq_qbar         : per (b, KV head, r) unit-normalise the r-th retained query of each head of the
+//                     group and average                                                 -> qbar
+#include "common.hip.h"
+#include "kernels.h"
+
+namespace quoka {
+
+constexpr int kSqTile = 64;     // tokens per tile
+constexpr int kSqThreads = 256;
+
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kSqThreads) void sq_partial_sums(Dims dm, const T* __restrict__ q, float* __restrict__ part,
+                                                             int n_tiles) {
+  constexpr int CG = D / 8;              // lanes per row (8 elements each)
+  constexpr int RPB = kSqThreads / CG;   // rows handled concurrently
+  const int tile = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int cg = threadIdx.x % CG, rr = threadIdx.x / CG;
+  const T* base = q + b * dm.qs[0] + h * dm.qs[1];
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int t0 = tile * kSqTile;
+  for (int r = rr; r < kSqTile; r += RPB) {
+    const int tok = t0 + r;
+    if (tok < dm.C) {
+      float v[8];
+      Elem<T>::load8(base + tok * dm.qs[2] + cg * 8, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += v[e];
+    }
+  }
+  __shared__ float red[RPB][D];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[rr][cg * 8 + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float s = 0.f;
+    for (int i = 0; i < RPB; ++i) s += red[i][threadIdx.x];
+    part[((size_t)(b * dm.n_q + h) * n_tiles + tile) * D + threadIdx.x] = s;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kSqThreads) void sq_cosine(Dims dm, const T* __restrict__ q, const float* __restrict__ part,
+                                                       float* __restrict__ cosv, int n_tiles) {
+  constexpr int CG = D / 8;
+  constexpr int RPB = kSqThreads / CG;
+  const int tile = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  __shared__ float mean[D];
+  __shared__ float mnorm;
+  if (threadIdx.x < D) {
+    const float* p = part + (size_t)(b * dm.n_q + h) * n_tiles * D + threadIdx.x;
+    float s = 0.f;
+    for (int i = 0; i < n_tiles; ++i) s += p[(size_t)i * D];
+    mean[threadIdx.x] = s / (float)dm.C;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float ss = 0.f;
+    for (int i = 0; i < D; ++i) ss += mean[i] * mean[i];
+    mnorm = fmaxf(sqrtf(ss), kNormEps);
+  }
+  __syncthreads();
+  const int cg = threadIdx.x % CG, rr = threadIdx.x / CG;
+  float m[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) m[e] = mean[cg * 8 + e];
+  const float mn = mnorm;
+  const T* base = q + b * dm.qs[0] + h * dm.qs[1];
+  const int t0 = tile * kSqTile;
+  for (int r = rr; r < kSqTile; r += RPB) {   // uniform trip count: shuffles below stay convergent
+    const int tok = t0 + r;
+    const int tk = tok < dm.C ? tok : dm.C - 1;
+    float v[8];
+    Elem<T>::load8(base + tk * dm.qs[2] + cg * 8, v);
+    float dot = 0.f, qq = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      dot += v[e] * m[e];
+      qq += v[e] * v[e];
+    }
+    dot = group_sum<CG>(dot);
+    qq = group_sum<CG>(qq);
+    if (cg == 0 && tok < dm.C) {
+      const float qn = fmaxf(sqrtf(qq), kNormEps);
+      cosv[(size_t)(b * dm.n_q + h) * dm.C + tok] = dot / (qn * mn) + 0.0f;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// One block per (b, q-head).  Dynamic LDS: C uint32 keys.
+__global__ __launch_bounds__(kSqThreads) void sq_select(Dims dm, const float* __restrict__ cosv, int32_t* __restrict__ q_idx,
+                                                       int n_keep) {
+  extern __shared__ uint32_t keys[];          // [C]
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t s_prefix, s_need;
+  __shared__ uint32_t wsum[kSqThreads / 64 + 1];
+  __shared__ uint32_t sel_key[128];
+  __shared__ uint32_t sel_idx[128];
+  __shared__ uint32_t n_lt;
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int C = dm.C;
+  const float* cv = cosv + (size_t)(b * dm.n_q + h) * C;
+  for (int i = threadIdx.x; i < C; i += kSqThreads) keys[i] = okey(cv[i]);
+  if (threadIdx.x == 0) {
+    s_prefix = 0;
+    s_need = (uint32_t)n_keep;  // rank (1-based, ascending) of the cut element
+    n_lt = 0;
+  }
+  __syncthreads();
+  uint32_t mask = 0;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    hist[threadIdx.x] = 0;   // kSqThreads == 256 bins
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+    for (int i = threadIdx.x; i < C; i += kSqThreads) {
+      const uint32_t k = keys[i];
+      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t need = s_need, bin = 0;
+      for (; bin < 256; ++bin) {   // ascending: the n_keep smallest
+        const uint32_t c = hist[bin];
+        if (need <= c) break;
+        need -= c;
+      }
+      s_need = need;
+      s_prefix = prefix | (bin << shift);
+    }
+    mask |= 255u << shift;
+    __syncthreads();
+  }
+  const uint32_t tau = s_prefix;      // key of the n_keep-th smallest cosine
+  const uint32_t need_eq = s_need;    // how many elements equal to tau are kept (lowest positions first)
+  // Ordered pass: thread t owns the contiguous positions [t*ipt, (t+1)*ipt).
+  const int ipt = (C + kSqThreads - 1) / kSqThreads;
+  const int lo = threadIdx.x * ipt;
+  const int hi = min(lo + ipt, C);
+  uint32_t c_eq = 0;
+  for (int i = lo; i < hi; ++i) c_eq += (keys[i] == tau);
+  uint32_t tot_eq;
+  uint32_t eq_rank = block_excl_scan<kSqThreads>(c_eq, wsum, &tot_eq);
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t k = keys[i];
+    bool take = k < tau;
+    if (k == tau) {
+      take = eq_rank < need_eq;
+      ++eq_rank;
+    }
+    if (take) {
+      const uint32_t slot = atomicAdd(&n_lt, 1u);   // slot order is irrelevant: ranks are recomputed below
+      if (slot < 128u) {
+        sel_key[slot] = k;
+        sel_idx[slot] = (uint32_t)i;
+      }
+    }
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < n_keep) {
+    const uint32_t k = sel_key[threadIdx.x], id = sel_idx[threadIdx.x];
+    int rank = 0;
+    for (int j = 0; j < n_keep; ++j) {
+      const uint32_t kj = sel_key[j], ij = sel_idx[j];
+      rank += (kj < k) || (kj == k && ij < id);
+    }
+    q_idx[(size_t)(b * dm.n_q + h) * n_keep + rank] = (int32_t)id;
+  }
+}
+
+__global__ void sq_identity(Dims dm, int32_t* __restrict__ q_idx, int n_keep) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  for (int i = threadIdx.x; i < n_keep; i += blockDim.x) q_idx[(size_t)(b * dm.n_q + h) * n_keep + i] = i;
+}
+
+// ---------------------------------------------------------------------------------------------
+// One wave per (r, kv, b): lanes own D/64 consecutive elements each.
+template <typename T, int D>
+__global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, const int32_t* __restrict__ q_idx,
+                                             float* __restrict__ qbar, int n_keep) {
+  constexpr int EPL = D / 64;
+  const int r = blockIdx.x, kv = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x;
+  float acc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+  for (int j = 0; j < dm.g; ++j) {
+    const int h = kv * dm.g + j;
+    const int tok = q_idx[(size_t)(b * dm.n_q + h) * n_keep + r];
+    const T* row = q + b * dm.qs[0] + h * dm.qs[1] + tok * dm.qs[2];
+    float v[EPL];
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      v[e] = Elem<T>::load1(row + lane * EPL + e);
+      ss += v[e] * v[e];
+    }
+    ss = group_sum<64>(ss);
+    const float nrm = fmaxf(sqrtf(ss), kNormEps);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] += v[e] / nrm;
+  }
+  float* out = qbar + ((size_t)(b * dm.n_kv + kv) * n_keep + r) * D;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) out[lane * EPL + e] = acc[e] / (float)dm.g;
+}
+
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D>
+static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, float* qbar, float* ws_part,
+                               float* ws_cos, hipStream_t st) {
+  const int n_keep = dm.n_ret < dm.C ? dm.n_ret : dm.C;
+  const T* qp = static_cast<const T*>(q);
+  if (dm.C > dm.n_ret) {
+    const int n_tiles = (dm.C + kSqTile - 1) / kSqTile;
+    dim3 grid(n_tiles, dm.n_q, dm.b);
+    hipLaunchKernelGGL((sq_partial_sums<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, n_tiles);
+    hipLaunchKernelGGL((sq_cosine<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, ws_cos, n_tiles);
+    hipLaunchKernelGGL(sq_select, dim3(dm.n_q, dm.b), dim3(kSqThreads), (size_t)dm.C * sizeof(uint32_t), st, dm,
+                       ws_cos, q_idx, n_keep);
+  } else {
+    hipLaunchKernelGGL(sq_identity, dim3(dm.n_q, dm.b), dim3(64), 0, st, dm, q_idx, n_keep);
+  }
+  hipLaunchKernelGGL((sq_qbar<T, D>), dim3(n_keep, dm.n_kv, dm.b), dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
+  return hipGetLastError();
+}
+
+size_t select_queries_ws_floats(const Dims& dm) {
+  const size_t n_tiles = (dm.C + kSqTile - 1) / kSqTile;
+  return (size_t)dm.b * dm.n_q * (n_tiles * dm.d + dm.C);
+}
+
+hipError_t launch_select_queries(const Dims& dm, int dtype, const void* q, int32_t* q_idx, float* qbar, float* ws,
+                                 hipStream_t st) {
+  const size_t n_tiles = (dm.C + kSqTile - 1) / kSqTile;
+  float* ws_part = ws;
+  float* ws_cos = ws + (size_t)dm.b * dm.n_q * n_tiles * dm.d;
+  if (dtype == QUOKA_F32) {
+    return dm.d == 64 ? launch_typed<float, 64>(dm, q, q_idx, qbar, ws_part, ws_cos, st)
+                      : launch_typed<float, 128>(dm, q, q_idx, qbar, ws_part, ws_cos, st);
+  }
+  return dm.d == 64 ? launch_typed<uint16_t, 64>(dm, q, q_idx, qbar, ws_part, ws_cos, st)
+                    : launch_typed<uint16_t, 128>(dm, q, q_idx, qbar, ws_part, ws_cos, st);
+}
+
+}  // namespace quoka

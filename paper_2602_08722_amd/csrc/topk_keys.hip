@@ -1,0 +1,322 @@
+// Top-B key selection per (sequence, KV head) (Alg. 1: I = topk(S-hat, B_SA); Eq. 3).
+//
+// Exact radix select on order-preserving uint32 images of the float scores, then an ordered
+// compaction so that indices come out in ascending position and equal scores go to the lower
+// position.  Integer work only: the result is deterministic and independent of the launch shape.
+//
+//   T_max <= kSmallMax : one 1024-thread block per head, keys held in LDS, one launch.
+//   larger             : several blocks per head.  Three histogram passes (11 + 11 + 10 bits, global
+//                        integer atomics) find the cut key; a count pass and an emit pass produce
+//                        the ordered index list.  Each pass re-derives the cut prefix from the
+//                        finished histograms, so no kernel waits on another block.
+#include "common.hip.h"
+#include "kernels.h"
+
+namespace quoka {
+
+constexpr int kSmallMax = 16384;
+constexpr int kSmallThreads = 1024;
+constexpr int kLgThreads = 256;
+constexpr int kLgTile = 2048;          // scores per block in the multi-block path
+constexpr int kBins = 2048;            // bins per histogram pass (11 bits; last pass uses 1024)
+
+__device__ __forceinline__ int radix_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ uint32_t radix_bins(int pass) { return pass == 2 ? 1024u : 2048u; }
+
+// ---------------------------------------------------------------------------------------------
+// Single-block path.
+__global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float* __restrict__ scores,
+                                                           const int32_t* __restrict__ kv_lens,
+                                                           const int32_t* __restrict__ budgets,
+                                                           int32_t* __restrict__ k_idx, int32_t* __restrict__ k_cnt) {
+  extern __shared__ uint32_t keys[];   // [T_max]
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t s_prefix, s_need;
+  __shared__ uint32_t wsum[kSmallThreads / 64 + 1];
+  const int kv = blockIdx.x, b = blockIdx.y;
+  const int T = max(0, min(kv_lens[b], dm.T_max));
+  const int B = max(0, min(min(budgets[b], T), dm.B_max));
+  int32_t* out = k_idx + (size_t)(b * dm.n_kv + kv) * dm.B_max;
+  if (threadIdx.x == 0) k_cnt[b * dm.n_kv + kv] = B;
+  if (B == 0) return;
+  if (B >= T) {
+    for (int i = threadIdx.x; i < T; i += kSmallThreads) out[i] = i;
+    return;
+  }
+  const float* sc = scores + (size_t)(b * dm.n_kv + kv) * dm.T_max;
+  for (int i = threadIdx.x; i < T; i += kSmallThreads) keys[i] = okey(sc[i]);
+  if (threadIdx.x == 0) {
+    s_prefix = 0;
+    s_need = (uint32_t)B;   // rank (1-based, descending) of the cut element
+  }
+  __syncthreads();
+  uint32_t mask = 0;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+    for (int i = threadIdx.x; i < T; i += kSmallThreads) {
+      const uint32_t k = keys[i];
+      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t need = s_need;
+      int bin = 255;
+      for (; bin > 0; --bin) {   // descending: the B largest
+        const uint32_t c = hist[bin];
+        if (need <= c) break;
+        need -= c;
+      }
+      s_need = need;
+      s_prefix = prefix | ((uint32_t)bin << shift);
+    }
+    mask |= 255u << shift;
+    __syncthreads();
+  }
+  const uint32_t tau = s_prefix, need_eq = s_need;
+  const int ipt = (T + kSmallThreads - 1) / kSmallThreads;
+  const int lo = min(threadIdx.x * ipt, (unsigned)T), hi = min(lo + ipt, T);
+  uint32_t c_gt = 0, c_eq = 0;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t k = keys[i];
+    c_gt += (k > tau);
+    c_eq += (k == tau);
+  }
+  uint32_t tot;
+  uint32_t p_gt = block_excl_scan<kSmallThreads>(c_gt, wsum, &tot);
+  uint32_t p_eq = block_excl_scan<kSmallThreads>(c_eq, wsum, &tot);
+  uint32_t pos = p_gt + min(p_eq, need_eq);
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t k = keys[i];
+    bool take = k > tau;
+    if (k == tau) {
+      take = p_eq < need_eq;
+      ++p_eq;
+    }
+    if (take) {
+      if (pos < (uint32_t)B) out[pos] = i;   // guard: a malformed score array cannot push writes past the budget
+      ++pos;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Multi-block path.  Workspace per head: hist[3][kBins] then tile counts [n_tiles][2].
+struct Cut {
+  uint32_t prefix;  // decided high bits of the cut key
+  uint32_t mask;    // which bits are decided
+  uint32_t need;    // rank of the cut inside the remaining candidates (1-based, descending)
+};
+
+// Whole block: locate the bin (scanning from the top) where the running count reaches `need`.
+// Returns (bin, need reduced by the counts above that bin).  `sh` is LDS scratch [kLgThreads + 2].
+__device__ __forceinline__ void find_bin(const uint32_t* __restrict__ hist, uint32_t nbins, uint32_t need,
+                                         uint32_t* sh, uint32_t* bin_out, uint32_t* need_out) {
+  // thread t owns bins [nbins - (t+1)*per, nbins - t*per): thread 0 has the highest bins.
+  const uint32_t per = nbins / kLgThreads;
+  const uint32_t top = nbins - threadIdx.x * per;   // exclusive upper bin
+  uint32_t mine = 0;
+  for (uint32_t i = 1; i <= per; ++i) mine += hist[top - i];
+  uint32_t tot;
+  const uint32_t above = block_excl_scan<kLgThreads>(mine, sh, &tot);   // count in all higher-bin threads
+  __syncthreads();
+  if (above < need && need <= above + mine) {   // exactly one thread (need <= total is guaranteed)
+    uint32_t rem = need - above;
+    uint32_t i = 1;
+    for (; i <= per; ++i) {
+      const uint32_t c = hist[top - i];
+      if (rem <= c) break;
+      rem -= c;
+    }
+    sh[kLgThreads] = top - i;
+    sh[kLgThreads + 1] = rem;
+  }
+  __syncthreads();
+  *bin_out = sh[kLgThreads];
+  *need_out = sh[kLgThreads + 1];
+  __syncthreads();
+}
+
+// Re-derive the cut after `npass` finished histogram passes.
+__device__ __forceinline__ Cut derive_cut(const uint32_t* __restrict__ hist, int npass, uint32_t B, uint32_t* sh) {
+  Cut c{0u, 0u, B};
+  for (int p = 0; p < npass; ++p) {
+    uint32_t bin, need;
+    find_bin(hist + p * kBins, radix_bins(p), c.need, sh, &bin, &need);
+    const int sft = radix_shift(p);
+    c.prefix |= bin << sft;
+    c.mask |= (radix_bins(p) - 1u) << sft;
+    c.need = need;
+  }
+  return c;
+}
+
+__global__ void topk_zero(uint32_t* __restrict__ p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+struct LgCtx {
+  int T, B;
+  const float* sc;
+  uint32_t* hist;
+  uint32_t* tcnt;
+};
+
+__device__ __forceinline__ LgCtx lg_ctx(const Dims& dm, const float* scores, const int32_t* kv_lens,
+                                        const int32_t* budgets, uint32_t* ws, int n_tiles) {
+  const int kv = blockIdx.y, b = blockIdx.z;
+  LgCtx c;
+  c.T = max(0, min(kv_lens[b], dm.T_max));
+  c.B = max(0, min(min(budgets[b], c.T), dm.B_max));
+  const size_t head = (size_t)(b * dm.n_kv + kv);
+  c.sc = scores + head * dm.T_max;
+  const size_t per_head = 3 * (size_t)kBins + 2 * (size_t)n_tiles;
+  c.hist = ws + head * per_head;
+  c.tcnt = c.hist + 3 * kBins;
+  return c;
+}
+
+template <int PASS>
+__global__ __launch_bounds__(kLgThreads) void topk_hist(Dims dm, const float* __restrict__ scores,
+                                                       const int32_t* __restrict__ kv_lens,
+                                                       const int32_t* __restrict__ budgets, uint32_t* __restrict__ ws,
+                                                       int n_tiles) {
+  __shared__ uint32_t lh[kBins];
+  __shared__ uint32_t sh[kLgThreads + 2];
+  const LgCtx c = lg_ctx(dm, scores, kv_lens, budgets, ws, n_tiles);
+  const int t0 = blockIdx.x * kLgTile;
+  if (c.B == 0 || c.B >= c.T || t0 >= c.T) return;   // block-uniform
+  const Cut cut = derive_cut(c.hist, PASS, (uint32_t)c.B, sh);
+  for (int i = threadIdx.x; i < kBins; i += kLgThreads) lh[i] = 0;
+  __syncthreads();
+  const int sft = radix_shift(PASS);
+  const uint32_t bm = radix_bins(PASS) - 1u;
+  const int t1 = min(t0 + kLgTile, c.T);
+  for (int i = t0 + threadIdx.x; i < t1; i += kLgThreads) {
+    const uint32_t k = okey(c.sc[i]);
+    if ((k & cut.mask) == cut.prefix) atomicAdd(&lh[(k >> sft) & bm], 1u);
+  }
+  __syncthreads();
+  uint32_t* gh = c.hist + PASS * kBins;
+  for (int i = threadIdx.x; i < kBins; i += kLgThreads) {
+    const uint32_t v = lh[i];
+    if (v) atomicAdd(&gh[i], v);
+  }
+}
+
+// EMIT == false: per-tile counts of (key > cut, key == cut).  EMIT == true: ordered output.
+template <bool EMIT>
+__global__ __launch_bounds__(kLgThreads) void topk_finish(Dims dm, const float* __restrict__ scores,
+                                                         const int32_t* __restrict__ kv_lens,
+                                                         const int32_t* __restrict__ budgets,
+                                                         uint32_t* __restrict__ ws, int n_tiles,
+                                                         int32_t* __restrict__ k_idx, int32_t* __restrict__ k_cnt) {
+  __shared__ uint32_t sh[kLgThreads + 2];
+  const LgCtx c = lg_ctx(dm, scores, kv_lens, budgets, ws, n_tiles);
+  const int kv = blockIdx.y, b = blockIdx.z;
+  const int t0 = blockIdx.x * kLgTile;
+  int32_t* out = k_idx + (size_t)(b * dm.n_kv + kv) * dm.B_max;
+  if (EMIT && blockIdx.x == 0 && threadIdx.x == 0) k_cnt[b * dm.n_kv + kv] = c.B;
+  if (c.B == 0 || t0 >= c.T) return;
+  const int t1 = min(t0 + kLgTile, c.T);
+  if (c.B >= c.T) {
+    if (EMIT)
+      for (int i = t0 + threadIdx.x; i < t1; i += kLgThreads) out[i] = i;
+    return;
+  }
+  const Cut cut = derive_cut(c.hist, 3, (uint32_t)c.B, sh);
+  const uint32_t tau = cut.prefix, need_eq = cut.need;
+  // thread t owns kLgTile / kLgThreads consecutive scores
+  constexpr int IPT = kLgTile / kLgThreads;
+  const int lo = t0 + threadIdx.x * IPT;
+  uint32_t kreg[IPT];
+  uint32_t c_gt = 0, c_eq = 0;
+#pragma unroll
+  for (int i = 0; i < IPT; ++i) {
+    const int t = lo + i;
+    const uint32_t k = t < t1 ? okey(c.sc[t]) : 0u;   // 0 is below every real key image except okey(-NaN); never > tau
+    kreg[i] = k;
+    c_gt += (t < t1) && (k > tau);
+    c_eq += (t < t1) && (k == tau);
+  }
+  uint32_t tot_gt, tot_eq;
+  uint32_t p_gt = block_excl_scan<kLgThreads>(c_gt, sh, &tot_gt);
+  uint32_t p_eq = block_excl_scan<kLgThreads>(c_eq, sh, &tot_eq);
+  if (!EMIT) {
+    if (threadIdx.x == 0) {
+      c.tcnt[2 * blockIdx.x] = tot_gt;
+      c.tcnt[2 * blockIdx.x + 1] = tot_eq;
+    }
+    return;
+  }
+  // counts of all earlier tiles (fixed order; at most a few hundred tiles)
+  uint32_t e_gt = 0, e_eq = 0;
+  for (int i = threadIdx.x; i < (int)blockIdx.x; i += kLgThreads) {
+    e_gt += c.tcnt[2 * i];
+    e_eq += c.tcnt[2 * i + 1];
+  }
+  __syncthreads();
+  uint32_t dummy;
+  (void)block_excl_scan<kLgThreads>(e_gt, sh, &tot_gt);
+  const uint32_t before_gt = tot_gt;
+  (void)block_excl_scan<kLgThreads>(e_eq, sh, &dummy);
+  const uint32_t before_eq = dummy;
+  p_eq += before_eq;
+  uint32_t pos = before_gt + p_gt + min(p_eq, need_eq);
+#pragma unroll
+  for (int i = 0; i < IPT; ++i) {
+    const int t = lo + i;
+    if (t < t1) {
+      const uint32_t k = kreg[i];
+      bool take = k > tau;
+      if (k == tau) {
+        take = p_eq < need_eq;
+        ++p_eq;
+      }
+      if (take) {
+        if (pos < (uint32_t)c.B) out[pos] = t;
+        ++pos;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+static inline int lg_tiles(const Dims& dm) { return (dm.T_max + kLgTile - 1) / kLgTile; }
+
+size_t topk_ws_words(const Dims& dm) {
+  if (dm.T_max <= kSmallMax) return 0;
+  return (size_t)dm.b * dm.n_kv * (3 * (size_t)kBins + 2 * (size_t)lg_tiles(dm));
+}
+
+hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* kv_lens, const int32_t* budgets,
+                            int32_t* k_idx, int32_t* k_cnt, uint32_t* ws, hipStream_t st) {
+  if (dm.T_max <= kSmallMax) {
+    const size_t lds = (size_t)(dm.T_max > 0 ? dm.T_max : 1) * sizeof(uint32_t);
+    static bool attr_done = false;
+    if (!attr_done) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_small),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kSmallMax * (int)sizeof(uint32_t));
+      if (e != hipSuccess) return e;
+      attr_done = true;
+    }
+    hipLaunchKernelGGL(topk_small, dim3(dm.n_kv, dm.b), dim3(kSmallThreads), lds, st, dm, scores, kv_lens, budgets,
+                       k_idx, k_cnt);
+    return hipGetLastError();
+  }
+  const int n_tiles = lg_tiles(dm);
+  const size_t words = topk_ws_words(dm);
+  hipLaunchKernelGGL(topk_zero, dim3(256), dim3(256), 0, st, ws, words);
+  dim3 grid(n_tiles, dm.n_kv, dm.b);
+  hipLaunchKernelGGL((topk_hist<0>), grid, dim3(kLgThreads), 0, st, dm, scores, kv_lens, budgets, ws, n_tiles);
+  hipLaunchKernelGGL((topk_hist<1>), grid, dim3(kLgThreads), 0, st, dm, scores, kv_lens, budgets, ws, n_tiles);
+  hipLaunchKernelGGL((topk_hist<2>), grid, dim3(kLgThreads), 0, st, dm, scores, kv_lens, budgets, ws, n_tiles);
+  hipLaunchKernelGGL((topk_finish<false>), grid, dim3(kLgThreads), 0, st, dm, scores, kv_lens, budgets, ws, n_tiles,
+                     k_idx, k_cnt);
+  hipLaunchKernelGGL((topk_finish<true>), grid, dim3(kLgThreads), 0, st, dm, scores, kv_lens, budgets, ws, n_tiles,
+                     k_idx, k_cnt);
+  return hipGetLastError();
+}
+
+}  // namespace quoka

@@ -1,0 +1,243 @@
+"""Stage-wise GPU parity: each HIP stage is fed the ORACLE's upstream output and compared with the oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import gen
+from oracle import quoka_oracle as O
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _pk():
+    import paper_2602_08722_amd as pk
+    pk.load_library()
+    return pk
+
+
+def _buffers(w, max_budget=None):
+    pk = _pk()
+    t = gen.to_torch(w, "cuda:0")
+    mb = max_budget if max_budget is not None else min(max(w.budgets), w.t_max)
+    buf = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain, max_budget=mb)
+    return buf
+
+
+SELECT_CASES = [
+    dict(dtype="f32", n_q=2, n_kv=1, d=64, chunk=128, n_retain=16),
+    dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=200, n_retain=64),     # ragged tile
+    dict(dtype="bf16", n_q=8, n_kv=2, d=64, chunk=77, n_retain=33),
+    dict(dtype="f32", n_q=4, n_kv=4, d=128, chunk=513, n_retain=128),
+    dict(dtype="bf16", n_q=4, n_kv=1, d=128, chunk=24, n_retain=32),      # C <= N_Q: identity
+    dict(dtype="bf16", n_q=2, n_kv=2, d=128, chunk=1, n_retain=16),       # single query (decode-like)
+    dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=2048, n_retain=128, batch=2),
+]
+
+
+@pytest.mark.parametrize("case", SELECT_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_select_queries(case):
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    w = gen.make_custom(batch=batch, kv_lens=[64] * batch, budgets=[8] * batch, seed=11, **case)
+    buf = _buffers(w)
+    buf.select_queries()
+    torch.cuda.synchronize()
+    q_idx = gen.from_torch(buf.q_idx)
+    qbar = gen.from_torch(buf.qbar)
+    n_keep = min(w.n_retain, w.chunk)
+    for b in range(w.batch):
+        cos = O.cos_to_mean(w.Q[b])
+        for h in range(w.n_q):
+            P.check_query_ranking(q_idx[b, h], cos[h], n_keep, what=f"b{b} h{h}")
+        # Q-bar from the GPU's own ranking (equal to the oracle's unless a documented tie swapped rows)
+        want = O.group_mean_queries(w.Q[b], q_idx[b], w.n_kv)
+        assert P.max_abs(qbar[b], want) <= P.TOL_QBAR
+
+
+SCORE_CASES = [
+    dict(dtype="f32", n_q=2, n_kv=1, d=64, chunk=128, n_retain=16, kv_lens=[1000]),
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=256, n_retain=64, kv_lens=[1500]),          # ragged tail tile
+    dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=256, n_retain=128, kv_lens=[4096 + 37]),
+    dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=256, n_retain=20, kv_lens=[700]),           # one partly padded block
+    dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=256, n_retain=96, kv_lens=[700]),           # 3 blocks -> padded 4th
+    dict(dtype="bf16", n_q=4, n_kv=4, d=64, chunk=64, n_retain=40, kv_lens=[900]),
+    dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=64, n_retain=32, kv_lens=[300, 0, 1029], batch=3),
+    dict(dtype="f32", n_q=4, n_kv=2, d=128, chunk=64, n_retain=32, kv_lens=[300, 5], batch=2),
+    dict(dtype="bf16", n_q=2, n_kv=1, d=128, chunk=8, n_retain=16, kv_lens=[40000]),            # several tiles per block
+]
+
+
+@pytest.mark.parametrize("case", SCORE_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_score_keys(case):
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    w = gen.make_custom(batch=batch, budgets=[8] * batch, seed=12, **case)
+    buf = _buffers(w)
+    # feed the oracle's Q-bar (rounded to float32, which is what the interface carries)
+    qbar_o = np.stack([O.group_mean_queries(w.Q[b], O.select_queries(w.Q[b], w.n_retain), w.n_kv)
+                       for b in range(w.batch)]).astype(np.float32)
+    buf.qbar.copy_(torch.from_numpy(qbar_o))
+    buf.scores.fill_(float("nan"))
+    buf.score_keys()
+    torch.cuda.synchronize()
+    sc = gen.from_torch(buf.scores)
+    worst = 0.0
+    for b in range(w.batch):
+        T = w.kv_lens[b]
+        want = O.key_scores_preagg(qbar_o[b].astype(np.float64), w.K[b][:, :T])
+        got = sc[b, :, :T]
+        assert not np.isnan(got).any()
+        worst = max(worst, P.max_abs(got, want))
+    assert worst <= P.TOL_SCORE, f"max |score - oracle| = {worst}"
+
+
+def _scores_for_topk(rng, n_kv, T, kind):
+    if kind == "normal":
+        return rng.standard_normal((n_kv, T)).astype(np.float32) * 0.2
+    if kind == "ties":          # heavy ties: only 17 distinct values
+        return (rng.integers(0, 17, size=(n_kv, T)).astype(np.float32) - 8) / 16
+    if kind == "const":
+        return np.full((n_kv, T), 0.25, dtype=np.float32)
+    if kind == "narrow":        # all scores inside one float exponent, differing in the low mantissa bits
+        base = np.float32(0.3)
+        ulp = np.spacing(base)
+        return (base + ulp * rng.integers(0, 64, size=(n_kv, T))).astype(np.float32)
+    if kind == "signed":        # positive, negative and zero scores
+        s = rng.standard_normal((n_kv, T)).astype(np.float32)
+        s[:, ::7] = 0.0
+        return s
+    raise ValueError(kind)
+
+
+TOPK_CASES = [
+    # (T list, budgets, T_max, kind)
+    ([1000], [100], 1000, "normal"),
+    ([1000], [100], 1000, "ties"),
+    ([1000], [999], 1000, "signed"),
+    ([777], [1], 1024, "normal"),
+    ([8192], [983], 8192, "normal"),
+    ([16384], [4000], 16384, "ties"),
+    ([500, 0, 1000], [50, 10, 2000], 1000, "normal"),       # empty sequence, budget > T
+    ([300], [0], 300, "normal"),                            # zero budget
+    ([64], [64], 64, "const"),
+    ([5000], [1234], 5000, "const"),
+    ([5000], [1234], 5000, "narrow"),
+    ([40000], [4800], 40000, "normal"),                     # multi-block path
+    ([40000], [4800], 40000, "ties"),
+    ([40000], [39999], 40000, "signed"),
+    ([70001], [12345], 70001, "narrow"),
+    ([20000, 33000, 0, 17000], [2000, 33000, 5, 1], 33000, "normal"),
+    ([131072], [8192], 131072, "normal"),
+    ([131072], [8192], 131072, "const"),
+]
+
+
+@pytest.mark.parametrize("case", TOPK_CASES, ids=lambda c: f"T{c[0]}-B{c[1]}-{c[3]}")
+def test_topk_keys_bit_exact(case):
+    pk = _pk()
+    Ts, budgets, t_max, kind = case
+    b, n_kv = len(Ts), 3
+    rng = np.random.default_rng(13)
+    scores = np.stack([_scores_for_topk(rng, n_kv, t_max, kind) for _ in range(b)])
+    # this stage reads no Q/K/V: describe the problem by hand instead of allocating a cache
+    dev = "cuda:0"
+    mb = min(max(budgets), t_max)
+    shape = pk.QuokaShape()
+    shape.batch, shape.n_q_heads, shape.n_kv_heads, shape.head_dim = b, n_kv, n_kv, 64
+    shape.chunk_len, shape.max_kv_len, shape.n_retain, shape.max_budget = 8, t_max, 4, mb
+    shape.dtype = pk.QUOKA_BF16
+    for name, tok in (("q_stride", 8), ("kv_stride", t_max), ("ck_stride", 8), ("o_stride", 8)):
+        setattr(shape, name, (ctypes.c_int64 * 3)(n_kv * tok * 64, tok * 64, 64))
+    ws = torch.empty(pk.quoka_workspace_bytes(shape), dtype=torch.uint8, device=dev)
+    sc = torch.from_numpy(scores).to(dev)
+    k_idx = torch.full((b, n_kv, max(mb, 1)), -7, dtype=torch.int32, device=dev)
+    k_cnt = torch.full((b, n_kv), -7, dtype=torch.int32, device=dev)
+    kv_lens = torch.tensor(Ts, dtype=torch.int32, device=dev)
+    bud = torch.tensor(budgets, dtype=torch.int32, device=dev)
+    for rep in range(2):   # second call reuses the workspace: it must be re-initialised by the library
+        pk.quoka_topk_keys(shape, sc, kv_lens, bud, k_idx, k_cnt, ws)
+        torch.cuda.synchronize()
+        gi, gc = gen.from_torch(k_idx), gen.from_torch(k_cnt)
+        for bi in range(b):
+            want = O.topk_keys(scores[bi][:, :Ts[bi]].astype(np.float64), budgets[bi])
+            for kv in range(n_kv):
+                n = want.shape[1]
+                assert gc[bi, kv] == n
+                assert np.array_equal(gi[bi, kv, :n], want[kv]), f"rep{rep} b{bi} kv{kv}"
+
+
+ATTN_CASES = [
+    dict(dtype="f32", n_q=2, n_kv=1, d=64, chunk=128, kv_lens=[1024], budgets=[128]),
+    dict(dtype="f32", n_q=4, n_kv=2, d=128, chunk=37, kv_lens=[100], budgets=[13]),
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=128, kv_lens=[1000], budgets=[200]),
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=100, kv_lens=[500], budgets=[65]),       # ragged rows and tiles
+    dict(dtype="bf16", n_q=4, n_kv=4, d=128, chunk=96, kv_lens=[300], budgets=[64]),        # group of 1
+    dict(dtype="bf16", n_q=4, n_kv=2, d=64, chunk=70, kv_lens=[300], budgets=[33]),         # head_dim 64, group of 2
+    dict(dtype="bf16", n_q=16, n_kv=2, d=128, chunk=64, kv_lens=[256], budgets=[128]),      # group of 8
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=64, kv_lens=[0], budgets=[16]),          # empty cache
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=1, kv_lens=[200], budgets=[50]),         # single query
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=80, kv_lens=[150, 0, 64], budgets=[40, 9, 64], batch=3),
+    dict(dtype="f32", n_q=4, n_kv=2, d=64, chunk=20, kv_lens=[90, 0], budgets=[30, 5], batch=2),
+]
+
+
+@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_sparse_and_dense_attention(case):
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    w = gen.make_custom(batch=batch, n_retain=8, seed=14, **case)
+    buf = _buffers(w)
+    tol = P.TOL_OUT[w.dtype]
+    # sparse: feed the oracle's index sets
+    k_idx_o = []
+    mb = buf.shape.max_budget
+    idx_host = np.zeros((w.batch, w.n_kv, max(mb, 1)), dtype=np.int32)
+    cnt_host = np.zeros((w.batch, w.n_kv), dtype=np.int32)
+    for b in range(w.batch):
+        T = w.kv_lens[b]
+        _, _, ki = O.quoka_select(w.Q[b], w.K[b][:, :T], w.n_retain, w.budgets[b])
+        k_idx_o.append(ki)
+        idx_host[b, :, :ki.shape[1]] = ki
+        cnt_host[b] = ki.shape[1]
+    buf.k_idx.copy_(torch.from_numpy(idx_host))
+    buf.k_cnt.copy_(torch.from_numpy(cnt_host))
+    buf.out.fill_(float("nan"))
+    buf.lse.fill_(float("nan"))
+    buf.sparse_attn()
+    torch.cuda.synchronize()
+    out, lse = gen.from_torch(buf.out), gen.from_torch(buf.lse)
+    for b in range(w.batch):
+        T = w.kv_lens[b]
+        want, want_lse = O.sparse_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], k_idx_o[b], w.Kc[b], w.Vc[b], True)
+        assert P.max_abs(out[b], want) <= tol, f"sparse b{b}: {P.max_abs(out[b], want)}"
+        assert P.max_abs(lse[b], want_lse) <= (1e-4 if w.dtype == "f32" else 2e-2)
+    # dense baseline
+    buf.out.fill_(float("nan"))
+    buf.dense_attn()
+    torch.cuda.synchronize()
+    out = gen.from_torch(buf.out)
+    for b in range(w.batch):
+        T = w.kv_lens[b]
+        want = O.dense_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], w.Kc[b], w.Vc[b])
+        assert P.max_abs(out[b], want) <= tol, f"dense b{b}: {P.max_abs(out[b], want)}"
+
+
+def test_sparse_attention_accepts_unsorted_indices_and_strided_views():
+    pk = _pk()
+    w = gen.make_custom(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=64, kv_lens=[400], budgets=[96], n_retain=8, seed=15)
+    t = gen.to_torch(w)
+    # K/V cache stored token-major ([b, T, n_kv, d]) and viewed as [b, n_kv, T, d]: non-trivial strides
+    k_tm = t["k"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    v_tm = t["v"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    buf = pk.ChunkBuffers(t["q"], k_tm, v_tm, t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain)
+    rng = np.random.default_rng(0)
+    idx = np.stack([rng.permutation(400)[:96] for _ in range(2)])[None].astype(np.int32)   # unsorted
+    buf.k_idx.copy_(torch.from_numpy(idx))
+    buf.k_cnt.fill_(96)
+    buf.sparse_attn()
+    torch.cuda.synchronize()
+    want = O.sparse_attn(w.Q[0], w.K[0], w.V[0], idx[0], w.Kc[0], w.Vc[0])
+    assert P.max_abs(gen.from_torch(buf.out)[0], want) <= P.TOL_OUT["bf16"]
