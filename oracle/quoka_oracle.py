@@ -150,20 +150,22 @@ def topk_keys(scores: np.ndarray, budget: int) -> np.ndarray:
 # Eq. 1-3 / Alg. 2: attention of the chunk over [selected past | chunk]
 # ---------------------------------------------------------------------------
 def _attend_head(q: np.ndarray, k_past: np.ndarray, v_past: np.ndarray,
-                 k_chunk: np.ndarray, v_chunk: np.ndarray):
+                 k_chunk: np.ndarray, v_chunk: np.ndarray, rows=None):
     """Softmax(q [k_past | k_chunk]^T / sqrt(d) + M) [v_past | v_chunk] for one head.
 
     M lets every chunk query see all past keys and chunk keys at positions <= its own.
-    Returns (O [C, d], lse [C]) with lse the natural-log normaliser of each row.
+    `rows` (optional) restricts the computation to those chunk positions (same arithmetic per row).
+    Returns (O [R, d], lse [R]) with lse the natural-log normaliser of each row.
     """
     C, d = q.shape
+    pos = np.arange(C) if rows is None else np.asarray(rows, dtype=np.int64)
     P = k_past.shape[0]
     k_all = np.concatenate([k_past, k_chunk], axis=0)
     v_all = np.concatenate([v_past, v_chunk], axis=0)
-    logits = (q @ k_all.T) / np.sqrt(d)                       # [C, P + C]
-    i = np.arange(C)[:, None]
+    logits = (q[pos] @ k_all.T) / np.sqrt(d)                  # [R, P + C]
+    i = pos[:, None]
     c = np.arange(C)[None, :]
-    mask = np.zeros((C, P + C), dtype=bool)
+    mask = np.zeros((pos.shape[0], P + C), dtype=bool)
     mask[:, P:] = c > i                                       # future chunk tokens
     logits = np.where(mask, -np.inf, logits)
     m = logits.max(axis=1, keepdims=True)
@@ -172,10 +174,12 @@ def _attend_head(q: np.ndarray, k_past: np.ndarray, v_past: np.ndarray,
     return (e / z) @ v_all, (m + np.log(z))[:, 0]
 
 
-def sparse_attn(Q, K, V, k_idx, Kc, Vc, return_lse: bool = False):
+def sparse_attn(Q, K, V, k_idx, Kc, Vc, return_lse: bool = False, rows=None, heads=None):
     """Chunk attention over gather(K, I), gather(V, I) and the chunk's own KV (Eq. 3, Alg. 2).
 
     k_idx: sequence of n_kv index arrays into the past cache (one per KV head).
+    rows / heads (optional): compute only these chunk positions / q-heads (for sampled checks at
+    sizes where the full result is too slow); outputs then have shape [len(heads), len(rows), d].
     """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
@@ -185,21 +189,23 @@ def sparse_attn(Q, K, V, k_idx, Kc, Vc, return_lse: bool = False):
     n_q, C, d = Q.shape
     n_kv = K.shape[0]
     g = n_q // n_kv
-    O = np.empty((n_q, C, d), dtype=np.float64)
-    L = np.empty((n_q, C), dtype=np.float64)
-    for h in range(n_q):
+    hs = list(range(n_q)) if heads is None else [int(h) for h in heads]
+    R = C if rows is None else len(rows)
+    O = np.empty((len(hs), R, d), dtype=np.float64)
+    L = np.empty((len(hs), R), dtype=np.float64)
+    for n, h in enumerate(hs):
         kv = h // g
         idx = np.asarray(k_idx[kv], dtype=np.int64)
-        O[h], L[h] = _attend_head(Q[h], K[kv][idx], V[kv][idx], Kc[kv], Vc[kv])
+        O[n], L[n] = _attend_head(Q[h], K[kv][idx], V[kv][idx], Kc[kv], Vc[kv], rows)
     return (O, L) if return_lse else O
 
 
-def dense_attn(Q, K, V, Kc, Vc, return_lse: bool = False):
+def dense_attn(Q, K, V, Kc, Vc, return_lse: bool = False, rows=None, heads=None):
     """Dense chunked-prefill attention of the chunk over the whole past cache (Eq. 2)."""
     K = np.asarray(K)
     T = K.shape[1]
     full = [np.arange(T, dtype=np.int64)] * K.shape[0]
-    return sparse_attn(Q, K, V, full, Kc, Vc, return_lse)
+    return sparse_attn(Q, K, V, full, Kc, Vc, return_lse, rows, heads)
 
 
 def quoka_select(Q, K, n_retain: int, budget: int):

@@ -1,0 +1,172 @@
+"""End-to-end GPU parity: the four sparse stages back to back (quoka_chunk_attn) against the oracle,
+at small sizes in full and at the full workload sizes on sampled rows."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+from oracle import quoka_oracle as O
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _pk():
+    import paper_2602_08722_amd as pk
+    pk.load_library()
+    return pk
+
+
+def _run(w, max_budget=None):
+    pk = _pk()
+    t = gen.to_torch(w, "cuda:0")
+    mb = max_budget if max_budget is not None else min(max(w.budgets), w.t_max)
+    buf = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain, max_budget=mb)
+    buf.out.fill_(float("nan"))
+    buf.chunk_attn()
+    torch.cuda.synchronize()
+    return buf
+
+
+def _check_selection(w, buf, b):
+    """Checks q_idx, scores and k_idx of sequence b against the oracle; returns the GPU's index lists."""
+    T = w.kv_lens[b]
+    n_keep = min(w.n_retain, w.chunk)
+    q_idx = gen.from_torch(buf.q_idx[b])
+    cos = O.cos_to_mean(w.Q[b])
+    swaps = sum(P.check_query_ranking(q_idx[h], cos[h], n_keep, what=f"b{b} h{h}") for h in range(w.n_q))
+    # scores against the oracle evaluated on the GPU's own retained queries (identical unless a tie swapped)
+    want_scores = O.key_scores(w.Q[b], q_idx, w.K[b][:, :T], w.n_kv)
+    got_scores = gen.from_torch(buf.scores[b])[:, :T]
+    assert P.max_abs(got_scores, want_scores) <= P.TOL_SCORE
+    cnt = gen.from_torch(buf.k_cnt[b])
+    k_idx = gen.from_torch(buf.k_idx[b])
+    subs = 0
+    sel = []
+    for kv in range(w.n_kv):
+        n = int(cnt[kv])
+        assert n == min(w.budgets[b], T)
+        subs += P.check_topk_set(k_idx[kv, :n], want_scores[kv], w.budgets[b], what=f"b{b} kv{kv}")
+        sel.append(k_idx[kv, :n])
+    return sel, swaps, subs
+
+
+def test_config1_end_to_end_fp32():
+    w = gen.make_workload("c1")
+    buf = _run(w)
+    sel, swaps, subs = _check_selection(w, buf, 0)
+    assert swaps == 0 and subs == 0            # no ties in this seeded case: the sets are bit-exact
+    q_idx_o, _, k_idx_o = O.quoka_select(w.Q[0], w.K[0], w.n_retain, w.budgets[0])
+    assert np.array_equal(gen.from_torch(buf.q_idx[0]), q_idx_o)
+    assert np.array_equal(np.stack(sel), k_idx_o)
+    assert set(w.notes["heavy_key_pos"]) <= set(sel[0].tolist())
+    want, want_lse = O.sparse_attn(w.Q[0], w.K[0], w.V[0], k_idx_o, w.Kc[0], w.Vc[0], return_lse=True)
+    assert P.max_abs(gen.from_torch(buf.out[0]), want) <= P.TOL_OUT["f32"]
+    assert P.max_abs(gen.from_torch(buf.lse[0]), want_lse) <= 1e-4
+
+
+E2E_CASES = [
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=192, n_retain=48, kv_lens=[3000], budgets=[360]),
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=100, n_retain=16, kv_lens=[777, 0, 2049, 130],
+         budgets=[93, 10, 245, 400], batch=4),
+    dict(dtype="bf16", n_q=4, n_kv=4, d=64, chunk=65, n_retain=65, kv_lens=[1000], budgets=[250]),
+    dict(dtype="f32", n_q=4, n_kv=2, d=128, chunk=48, n_retain=8, kv_lens=[500, 33], budgets=[60, 20], batch=2),
+    dict(dtype="bf16", n_q=16, n_kv=2, d=128, chunk=130, n_retain=128, kv_lens=[20000], budgets=[2400]),
+]
+
+
+@pytest.mark.parametrize("case", E2E_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_chunk_attn_end_to_end(case):
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    w = gen.make_custom(batch=batch, seed=21, **case)
+    buf = _run(w)
+    out = gen.from_torch(buf.out)
+    for b in range(w.batch):
+        T = w.kv_lens[b]
+        sel, _, _ = _check_selection(w, buf, b)
+        want = O.sparse_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], sel, w.Kc[b], w.Vc[b])
+        assert P.max_abs(out[b], want) <= P.TOL_OUT[w.dtype], f"b{b}: {P.max_abs(out[b], want)}"
+
+
+def test_full_budget_reproduces_dense_and_runs_are_deterministic():
+    w = gen.make_custom(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=96, n_retain=16, kv_lens=[600, 300],
+                        budgets=[600, 9999], batch=2, seed=22)
+    buf = _run(w, max_budget=600)
+    sparse_out = buf.out.clone()
+    cnt = gen.from_torch(buf.k_cnt)
+    assert cnt.tolist() == [[600, 600], [300, 300]]
+    for b, T in enumerate(w.kv_lens):
+        assert np.array_equal(gen.from_torch(buf.k_idx[b])[:, :T], np.tile(np.arange(T), (2, 1)))
+    dense_out = torch.empty_like(buf.out)
+    buf.dense_attn(out=dense_out)
+    torch.cuda.synchronize()
+    # same kernel, same key order, same arithmetic: identical bits
+    assert torch.equal(sparse_out.view(torch.int16), dense_out.view(torch.int16))
+    want = np.stack([O.dense_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], w.Kc[b], w.Vc[b])
+                     for b, T in enumerate(w.kv_lens)])
+    assert P.max_abs(gen.from_torch(dense_out), want) <= P.TOL_OUT["bf16"]
+    # determinism: a second run gives identical indices and output bits
+    k_idx1, q_idx1 = buf.k_idx.clone(), buf.q_idx.clone()
+    buf.chunk_attn()
+    torch.cuda.synchronize()
+    assert torch.equal(buf.q_idx, q_idx1)
+    for b, T in enumerate(w.kv_lens):
+        assert torch.equal(buf.k_idx[b, :, :T], k_idx1[b, :, :T])
+    assert torch.equal(buf.out.view(torch.int16), sparse_out.view(torch.int16))
+
+
+def _sample_rows(C, n, seed):
+    rng = np.random.default_rng(seed)
+    fixed = {0, 31, 32, 63, 64, C - 1, C - 33 if C > 33 else 0}
+    rows = set(int(r) for r in fixed if 0 <= r < C)
+    while len(rows) < min(n, C):
+        rows.add(int(rng.integers(0, C)))
+    return sorted(rows)
+
+
+def _full_size_check(w, n_rows, dense_heads, dense_rows):
+    buf = _run(w)
+    out = gen.from_torch(buf.out)
+    total_subs = 0
+    for b in range(w.batch):
+        T = w.kv_lens[b]
+        sel, swaps, subs = _check_selection(w, buf, b)
+        total_subs += subs
+        rows = _sample_rows(w.chunk, n_rows, seed=100 + b)
+        want = O.sparse_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], sel, w.Kc[b], w.Vc[b], rows=rows)
+        err = P.max_abs(out[b][:, rows], want)
+        assert err <= P.TOL_OUT[w.dtype], f"sparse b{b}: {err}"
+    # dense baseline on a few heads / rows
+    dense_out = torch.empty_like(buf.out)
+    buf.dense_attn(out=dense_out)
+    torch.cuda.synchronize()
+    dout = gen.from_torch(dense_out)
+    for b in range(w.batch):
+        T = w.kv_lens[b]
+        rows = _sample_rows(w.chunk, dense_rows, seed=200 + b)
+        want = O.dense_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], w.Kc[b], w.Vc[b], rows=rows, heads=dense_heads)
+        err = P.max_abs(dout[b][dense_heads][:, rows], want)
+        assert err <= P.TOL_OUT[w.dtype], f"dense b{b}: {err}"
+    return total_subs
+
+
+def test_config2_full_size():
+    w = gen.make_workload("c2")
+    _full_size_check(w, n_rows=128, dense_heads=[0, 13, 31], dense_rows=48)
+
+
+def test_config3_full_size():
+    w = gen.make_workload("c3")
+    _full_size_check(w, n_rows=64, dense_heads=[5, 30], dense_rows=24)
+
+
+def test_config4_full_size():
+    w = gen.make_workload("c4")
+    _full_size_check(w, n_rows=48, dense_heads=[17], dense_rows=16)
+
+
+@pytest.mark.parametrize("n_retain,frac", [(32, 0.04), (64, 0.12), (128, 0.25)])
+def test_config5_ragged_batch(n_retain, frac):
+    w = gen.make_workload("c5", n_retain=n_retain, budget_frac=frac)
+    _full_size_check(w, n_rows=24, dense_heads=[9], dense_rows=8)

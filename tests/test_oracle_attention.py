@@ -156,3 +156,15 @@ def test_quoka_prefill_with_huge_budget_equals_full_causal():
     assert np.max(np.abs(sparse - dense)) > 1e-3
     # first chunk has no past: identical regardless of budget
     assert np.array_equal(sparse[:, :8], dense[:, :8])
+
+
+def test_row_and_head_sampling_matches_the_full_result():
+    n_q, n_kv, T, C, d = 4, 2, 30, 12, 8
+    Q, K, V = _rand(40, n_q, C, d), _rand(41, n_kv, T, d), _rand(42, n_kv, T, d)
+    Kc, Vc = _rand(43, n_kv, C, d), _rand(44, n_kv, C, d)
+    sel = [np.arange(0, T, 2), np.arange(1, T, 3)]
+    full, lse = O.sparse_attn(Q, K, V, sel, Kc, Vc, return_lse=True)
+    rows, heads = [0, 5, 11], [1, 2]
+    part, lse_p = O.sparse_attn(Q, K, V, sel, Kc, Vc, return_lse=True, rows=rows, heads=heads)
+    assert np.allclose(part, full[heads][:, rows], atol=1e-15)
+    assert np.allclose(lse_p, lse[heads][:, rows], atol=1e-15)
