@@ -85,42 +85,40 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
 
   const int cg = tid % CG, r0 = tid / CG;
   int rows[NLD];       // resolved source rows of the tile to be issued next
-  uint4 RK[NLD], RV[NLD];
+  u32x4 RK[NLD], RV[NLD];
 
-  auto resolve = [&](int it) {
-    if (it >= n_tiles) return;
-    if (it < n_ct) {
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int n = min(it * kBN + r0 + RPI * i, n_cache - 1);   // tail slots repeat a real row (masked later)
-        rows[i] = sparse ? kidx[n] : n;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) rows[i] = min((it - n_ct) * kBN + r0 + RPI * i, C - 1);
-    }
-  };
-  auto issue = [&](int it) {
-    if (it < n_ct) {
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const size_t off = (size_t)rows[i] * dm.kvs[2] + cg * 8;
-        RK[i] = *reinterpret_cast<const uint4*>(kcache + off);
-        RV[i] = *reinterpret_cast<const uint4*>(vcache + off);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const size_t off = (size_t)rows[i] * dm.cks[2] + cg * 8;
-        RK[i] = *reinterpret_cast<const uint4*>(kchunk + off);
-        RV[i] = *reinterpret_cast<const uint4*>(vchunk + off);
-      }
-    }
-  };
+  // Source rows of a tile are resolved one tile ahead of the loads that use them, so the dependent
+  // index -> row fetch of the gather never sits on the critical path.  (Written as macros, not lambdas:
+  // the staging registers must stay in VGPRs.)
+#define QUOKA_RESOLVE(IT)                                                                          \
+  do {                                                                                             \
+    const int it_ = (IT);                                                                          \
+    if (it_ < n_tiles) {                                                                           \
+      const bool cache_ = it_ < n_ct;                                                              \
+      const int base_ = cache_ ? it_ * kBN : (it_ - n_ct) * kBN;                                   \
+      const int last_ = cache_ ? n_cache - 1 : C - 1;                                              \
+      _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                                            \
+        const int n_ = min(base_ + r0 + RPI * i, last_); /* tail slots repeat a real row */        \
+        rows[i] = (cache_ && sparse) ? kidx[n_] : n_;                                              \
+      }                                                                                            \
+    }                                                                                              \
+  } while (0)
+#define QUOKA_ISSUE(IT)                                                                            \
+  do {                                                                                             \
+    const bool cache_ = (IT) < n_ct;                                                               \
+    const uint16_t* kb_ = cache_ ? kcache : kchunk;                                                \
+    const uint16_t* vb_ = cache_ ? vcache : vchunk;                                                \
+    const long long st_ = cache_ ? dm.kvs[2] : dm.cks[2];                                          \
+    _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                                              \
+      const size_t off_ = (size_t)rows[i] * st_ + cg * 8;                                          \
+      RK[i] = *reinterpret_cast<const u32x4*>(kb_ + off_);                                         \
+      RV[i] = *reinterpret_cast<const u32x4*>(vb_ + off_);                                         \
+    }                                                                                              \
+  } while (0)
 
-  resolve(0);
-  issue(0);
-  resolve(1);
+  QUOKA_RESOLVE(0);
+  QUOKA_ISSUE(0);
+  QUOKA_RESOLVE(1);
 
   f32x16 o[DB];
 #pragma unroll
@@ -138,13 +136,13 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int rl = r0 + RPI * i;
-      *reinterpret_cast<uint4*>(kt + rl * LD + cg * 8) = RK[i];
-      *reinterpret_cast<uint4*>(vt + rl * LD + cg * 8) = RV[i];
+      *reinterpret_cast<u32x4*>(kt + rl * LD + cg * 8) = RK[i];
+      *reinterpret_cast<u32x4*>(vt + rl * LD + cg * 8) = RV[i];
     }
     __syncthreads();   // tile `it` visible; every wave is past its reads of the other buffer's previous use
     if (it + 1 < n_tiles) {
-      issue(it + 1);
-      resolve(it + 2);
+      QUOKA_ISSUE(it + 1);
+      QUOKA_RESOLVE(it + 2);
     }
 
     const bool is_chunk = it >= n_ct;
@@ -260,6 +258,9 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
     }
   }
 }
+
+#undef QUOKA_RESOLVE
+#undef QUOKA_ISSUE
 
 template <int D>
 static hipError_t launch_d(const Dims& dm, const AttnArgs& a, hipStream_t st) {

@@ -13,6 +13,8 @@ constexpr int kWave = 64;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // Kernel-side view of quoka_shape (plain copy; passed by value).
 struct Dims {
@@ -110,6 +112,43 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t x, uint32_t* wsum, 
   __syncthreads();
   *total = wsum[NT / 64];
   return wsum[w] + inc - x;
+}
+
+// One wave (the caller guarantees threadIdx.x < 64 and all 64 lanes active) walks a 256-bin LDS
+// histogram in descending (DESC) or ascending bin order and finds the bin in which the running count
+// reaches `need` (1-based rank, need <= total count).  The one lane that finds it ORs the bin, shifted,
+// into *prefix_io and stores the rank remaining inside the bin to *need_out.
+template <bool DESC>
+__device__ __forceinline__ void wave_find_bin256(const uint32_t* hist, uint32_t need, int shift, uint32_t* prefix_io,
+                                                 uint32_t* need_out) {
+  const int lane = threadIdx.x & 63;
+  uint32_t c[4];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int o = 4 * lane + j;   // position in scan order
+    c[j] = hist[DESC ? 255 - o : o];
+    sum += c[j];
+  }
+  uint32_t inc = sum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t y = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += y;
+  }
+  const uint32_t excl = inc - sum;
+  if (excl < need && need <= inc) {   // exactly one lane
+    uint32_t rem = need - excl;
+    int j = 0;
+#pragma unroll
+    for (; j < 3; ++j) {
+      if (rem <= c[j]) break;
+      rem -= c[j];
+    }
+    const int o = 4 * lane + j;
+    *prefix_io |= (uint32_t)(DESC ? 255 - o : o) << shift;
+    *need_out = rem;
+  }
 }
 
 }  // namespace quoka

@@ -31,9 +31,9 @@ struct ScoreCfg {
   static constexpr size_t kLdsBytes = 2 * kTileBytes + 2 * kScTile * 4 + QB * kScTile * 4;
 };
 
-__device__ __forceinline__ float sumsq_bf16x8(const uint4& r) {
+__device__ __forceinline__ float sumsq_bf16x8(const u32x4& r) {
   float s = 0.f;
-  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+  const uint32_t w[4] = {r[0], r[1], r[2], r[3]};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const float a = __uint_as_float(w[i] << 16), b = __uint_as_float(w[i] & 0xFFFF0000u);
@@ -94,14 +94,14 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
   float* sc = scores + (size_t)(b * dm.n_kv + kv) * dm.T_max;
   const int cg = tid % CG, r0 = tid / CG;
 
-  uint4 R[NLD];
+  u32x4 R[NLD];
   auto issue = [&](int it) {
     const int t0 = t_begin + it * kScTile;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       int row = t0 + r0 + RPI * i;
       row = row < T ? row : T - 1;  // tail rows re-read the last valid key; their scores are not stored
-      R[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)row * dm.kvs[2] + cg * 8);
+      R[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)row * dm.kvs[2] + cg * 8);
     }
   };
   issue(0);
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int rl = r0 + RPI * i;
-      *reinterpret_cast<uint4*>(tl + rl * LD + cg * 8) = R[i];
+      *reinterpret_cast<u32x4*>(tl + rl * LD + cg * 8) = R[i];
       const float ss = group_sum<CG>(sumsq_bf16x8(R[i]));
       if (cg == 0) ssq[buf * kScTile + rl] = ss;
     }

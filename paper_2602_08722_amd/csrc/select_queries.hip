@@ -126,16 +126,7 @@ __global__ __launch_bounds__(kSqThreads) void sq_select(Dims dm, const float* __
       if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t need = s_need, bin = 0;
-      for (; bin < 256; ++bin) {   // ascending: the n_keep smallest
-        const uint32_t c = hist[bin];
-        if (need <= c) break;
-        need -= c;
-      }
-      s_need = need;
-      s_prefix = prefix | (bin << shift);
-    }
+    if (threadIdx.x < 64) wave_find_bin256<false>(hist, s_need, shift, &s_prefix, &s_need);   // ascending: smallest
     mask |= 255u << shift;
     __syncthreads();
   }

@@ -60,17 +60,7 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
       if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t need = s_need;
-      int bin = 255;
-      for (; bin > 0; --bin) {   // descending: the B largest
-        const uint32_t c = hist[bin];
-        if (need <= c) break;
-        need -= c;
-      }
-      s_need = need;
-      s_prefix = prefix | ((uint32_t)bin << shift);
-    }
+    if (threadIdx.x < 64) wave_find_bin256<true>(hist, s_need, shift, &s_prefix, &s_need);   // descending: B largest
     mask |= 255u << shift;
     __syncthreads();
   }
