@@ -174,16 +174,27 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
         }
     }
     // ---- online softmax -----------------------------------------------------------------------
+    // The reference point m_run only moves when the tile maximum exceeds it by more than 2^kLazy:
+    // exp2(s - m_run) then stays below 2^kLazy, and rescaling the accumulators becomes rare.
     float mx = -INFINITY;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
-    mx = fmaxf(mx, other_half(mx));
-    const float m_new = fmaxf(m_run, mx * sl2);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-    m_run = m_new;
+    mx = fmaxf(mx, other_half(mx)) * sl2;
+    constexpr float kLazy = 8.0f;
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazy) != 0) {   // wave-uniform branch
+      const float m_new = (mx > m_run + kLazy) ? mx : m_run;       // -inf + 8 = -inf: the first visible tile lands here
+      const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_fin);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int c = 0; c < DB; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[c][v] *= alpha;
+    }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
     float psum = 0.f;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
@@ -193,11 +204,7 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
         s[nb][v] = p;
         psum += p;
       }
-    l_run = fmaf(l_run, alpha, psum);
-#pragma unroll
-    for (int c = 0; c < DB; ++c)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[c][v] *= alpha;
+    l_run += psum;
     // ---- O^T += V^T P^T -----------------------------------------------------------------------
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
@@ -207,27 +214,27 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
 #pragma unroll
         for (int e = 0; e < 8; ++e) pb[e] = (__bf16)s[nb][8 * t + e];
         // the 8 keys behind this lane's k-slots: 16t + 8*(e/4) + 4*hf + e%4 of block nb
-        uint16_t ve[8][DB];
+        uint32_t vr[8][DB / 2];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int kk = nb * 32 + 16 * t + 8 * (e / 4) + 4 * hf + (e % 4);
           const uint16_t* vp = vt + kk * LD + DB * li;
           if constexpr (DB == 4) {
-            const uint2 r = *reinterpret_cast<const uint2*>(vp);
-            ve[e][0] = (uint16_t)(r.x & 0xFFFFu); ve[e][1] = (uint16_t)(r.x >> 16);
-            ve[e][2] = (uint16_t)(r.y & 0xFFFFu); ve[e][3] = (uint16_t)(r.y >> 16);
+            const u32x2 r = *reinterpret_cast<const u32x2*>(vp);
+            vr[e][0] = r[0];
+            vr[e][1] = r[1];
           } else {
-            const uint32_t r = *reinterpret_cast<const uint32_t*>(vp);
-            ve[e][0] = (uint16_t)(r & 0xFFFFu); ve[e][1] = (uint16_t)(r >> 16);
+            vr[e][0] = *reinterpret_cast<const uint32_t*>(vp);
           }
         }
 #pragma unroll
         for (int c = 0; c < DB; ++c) {
-          uint4 packed;
-          packed.x = (uint32_t)ve[0][c] | ((uint32_t)ve[1][c] << 16);
-          packed.y = (uint32_t)ve[2][c] | ((uint32_t)ve[3][c] << 16);
-          packed.z = (uint32_t)ve[4][c] | ((uint32_t)ve[5][c] << 16);
-          packed.w = (uint32_t)ve[6][c] | ((uint32_t)ve[7][c] << 16);
+          // dim block c takes 16-bit element c of every read: byte-permute pairs of keys into one dword
+          const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+          u32x4 packed;
+#pragma unroll
+          for (int p2 = 0; p2 < 4; ++p2)
+            packed[p2] = __builtin_amdgcn_perm(vr[2 * p2 + 1][c / 2], vr[2 * p2][c / 2], sel);
           const bf16x8 vop = __builtin_bit_cast(bf16x8, packed);
           o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pb, o[c], 0, 0, 0);
         }
