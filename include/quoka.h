@@ -25,7 +25,8 @@
  *       QUOKA_EUNSUPPORTED head_dim not in {64,128}, unknown dtype, size beyond a stated limit
  *       QUOKA_EWORKSPACE   workspace smaller than quoka_workspace_bytes() says (or misaligned)
  *       QUOKA_EHIP         the HIP runtime refused a launch
- *   - Limits: n_retain <= 128, chunk_len <= 8192, max_kv_len < 2^24, max_budget <= max_kv_len.
+ *   - Limits: n_retain <= 128, chunk_len <= 8192, max_kv_len < 2^24, max_budget <= max_kv_len,
+ *     n_q_heads / n_kv_heads <= 16.
  *   - kv_lens[b] == 0 is legal (first chunk): nothing is selected and attention is plain causal
  *     attention over the chunk.  A budget >= kv_lens[b] selects the whole cache.
  *   - Inputs are assumed finite (no NaN/Inf).

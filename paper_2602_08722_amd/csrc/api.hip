@@ -10,6 +10,7 @@ namespace {
 using quoka::Dims;
 
 constexpr int kMaxRetain = 128;
+constexpr int kMaxGroup = 16;   // q-heads per KV head
 constexpr int kMaxChunk = 8192;
 constexpr int kMaxKv = 1 << 24;
 constexpr size_t kAlign = 256;
@@ -32,6 +33,7 @@ quoka_status check_shape(const quoka_shape* s, Dims* dm) {
   if (s->dtype != QUOKA_F32 && s->dtype != QUOKA_BF16) return QUOKA_EUNSUPPORTED;
   if (s->head_dim != 64 && s->head_dim != 128) return QUOKA_EUNSUPPORTED;
   if (s->n_retain > kMaxRetain || s->chunk_len > kMaxChunk || s->max_kv_len >= kMaxKv) return QUOKA_EUNSUPPORTED;
+  if (s->n_q_heads / s->n_kv_heads > kMaxGroup) return QUOKA_EUNSUPPORTED;
   if ((long long)s->batch * s->n_q_heads > 65535 || s->batch > 65535) return QUOKA_EUNSUPPORTED;
   const int64_t* strides[4] = {s->q_stride, s->kv_stride, s->ck_stride, s->o_stride};
   for (const int64_t* st : strides) {

@@ -100,14 +100,16 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t x, uint32_t* wsum, 
   __syncthreads();  // protect wsum against a previous use
   if (lane == 63) wsum[w] = inc;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t run = 0;
-    for (int i = 0; i < NT / 64; ++i) {
-      const uint32_t t = wsum[i];
-      wsum[i] = run;
-      run += t;
+  if (w == 0) {   // wave 0 scans the NT/64 wave totals
+    const uint32_t t = lane < NT / 64 ? wsum[lane] : 0u;
+    uint32_t run = t;
+#pragma unroll
+    for (int o = 1; o < NT / 64; o <<= 1) {
+      const uint32_t y = __shfl_up(run, o, kWave);
+      if (lane >= o) run += y;
     }
-    wsum[NT / 64] = run;
+    if (lane < NT / 64) wsum[lane] = run - t;
+    if (lane == NT / 64 - 1) wsum[NT / 64] = run;
   }
   __syncthreads();
   *total = wsum[NT / 64];

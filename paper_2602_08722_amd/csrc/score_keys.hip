@@ -66,6 +66,23 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
   const int qb = w % QB, kg = w / QB;
   const int li = lane & 31, hf = lane >> 5;
 
+  const uint16_t* kbase = kc + b * dm.kvs[0] + kv * dm.kvs[1];
+  float* sc = scores + (size_t)(b * dm.n_kv + kv) * dm.T_max;
+  const int cg = tid % CG, r0 = tid / CG;
+
+  u32x4 R[NLD];
+  auto issue = [&](int it) {
+    const int t0 = t_begin + it * kScTile;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      int row = t0 + r0 + RPI * i;
+      row = row < T ? row : T - 1;  // tail rows re-read the last valid key; their scores are not stored
+      R[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)row * dm.kvs[2] + cg * 8);
+    }
+  };
+  issue(0);   // the first K tile is in flight while the query operands are prepared
+
+
   // Query operands: this wave's 32 query rows, split into three bf16 terms.
   bf16x8 a_hi[KS], a_mid[KS], a_lo[KS];
   {
@@ -89,22 +106,6 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
       }
     }
   }
-
-  const uint16_t* kbase = kc + b * dm.kvs[0] + kv * dm.kvs[1];
-  float* sc = scores + (size_t)(b * dm.n_kv + kv) * dm.T_max;
-  const int cg = tid % CG, r0 = tid / CG;
-
-  u32x4 R[NLD];
-  auto issue = [&](int it) {
-    const int t0 = t_begin + it * kScTile;
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      int row = t0 + r0 + RPI * i;
-      row = row < T ? row : T - 1;  // tail rows re-read the last valid key; their scores are not stored
-      R[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)row * dm.kvs[2] + cg * 8);
-    }
-  };
-  issue(0);
 
   for (int it = 0; it < n_tiles; ++it) {
     const int buf = it & 1;

@@ -1,12 +1,13 @@
 // Query sub-selection and group pre-aggregation (Alg. 1, first block and the normalise / group-mean steps;
-// Sec. 3.1, 3.3).  Four small kernels:
+// Sec. 3.1, 3.3).
+// Memory reads are spread over the whole chip (one compute unit alone cannot pull a head's queries at more
+// than a few tens of GB/s), and every kernel requests all the rows it needs before it uses the first.
 //   sq_partial_sums : per (b, q-head, token tile) column sums of Q                     -> ws.part
 //   sq_cosine       : per (b, q-head, token tile) mean query from the partials (fixed order, so the
 //                     result is bit-reproducible), then CosSim(q_i, M_Q) for the tile   -> ws.cos
-//   sq_select       : per (b, q-head) the N' lowest cosines in rank order (LDS radix select + rank
-//                     by counting)                                                      -> q_idx
-//   sq_qbar         : per (b, KV head, r) unit-normalise the r-th retained query of each head of the
-//                     group and average                                                 -> qbar
+//   sq_select_qbar  : per (b, KV head) the N' lowest cosines of each head of the group in rank order
+//                     (LDS radix select + rank by counting) -> q_idx, then the group mean of the
+//                     unit-normalised retained queries                                  -> qbar
 #include "common.hip.h"
 #include "kernels.h"
 
@@ -58,7 +59,14 @@ __global__ __launch_bounds__(kSqThreads) void sq_cosine(Dims dm, const T* __rest
   if (threadIdx.x < D) {
     const float* p = part + (size_t)(b * dm.n_q + h) * n_tiles * D + threadIdx.x;
     float s = 0.f;
-    for (int i = 0; i < n_tiles; ++i) s += p[(size_t)i * D];
+    for (int i0 = 0; i0 < n_tiles; i0 += 8) {   // 8 partials requested at a time, summed in tile order
+      float t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = p[(size_t)min(i0 + u, n_tiles - 1) * D];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (i0 + u < n_tiles) s += t[u];
+    }
     mean[threadIdx.x] = s / (float)dm.C;
   }
   __syncthreads();
@@ -96,112 +104,130 @@ __global__ __launch_bounds__(kSqThreads) void sq_cosine(Dims dm, const T* __rest
 }
 
 // ---------------------------------------------------------------------------------------------
-// One block per (b, q-head).  Dynamic LDS: C uint32 keys.
-__global__ __launch_bounds__(kSqThreads) void sq_select(Dims dm, const float* __restrict__ cosv, int32_t* __restrict__ q_idx,
-                                                       int n_keep) {
+// One 1024-thread block per (b, KV head): for each q-head of the group, the N' lowest cosines in rank
+// order (LDS radix select, 8 bits per pass, ties to the lower position; then rank by counting), and, with
+// the group's index lists still in LDS, the group mean of the unit-normalised retained queries.
+// Dynamic LDS: C uint32 keys.
+constexpr int kSelThreads = 1024;
+constexpr int kMaxGroup = 16;
+constexpr int kMaxKeep = 128;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kSelThreads) void sq_select_qbar(Dims dm, const T* __restrict__ q,
+                                                             const float* __restrict__ cosv,
+                                                             int32_t* __restrict__ q_idx, float* __restrict__ qbar,
+                                                             int n_keep) {
+  constexpr int NW = kSelThreads / 64;
+  constexpr int EPL = D / 64;
   extern __shared__ uint32_t keys[];          // [C]
   __shared__ uint32_t hist[256];
-  __shared__ uint32_t s_prefix, s_need;
-  __shared__ uint32_t wsum[kSqThreads / 64 + 1];
-  __shared__ uint32_t sel_key[128];
-  __shared__ uint32_t sel_idx[128];
-  __shared__ uint32_t n_lt;
-  const int h = blockIdx.x, b = blockIdx.y;
-  const int C = dm.C;
-  const float* cv = cosv + (size_t)(b * dm.n_q + h) * C;
-  for (int i = threadIdx.x; i < C; i += kSqThreads) keys[i] = okey(cv[i]);
-  if (threadIdx.x == 0) {
-    s_prefix = 0;
-    s_need = (uint32_t)n_keep;  // rank (1-based, ascending) of the cut element
-    n_lt = 0;
-  }
-  __syncthreads();
-  uint32_t mask = 0;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    hist[threadIdx.x] = 0;   // kSqThreads == 256 bins
-    __syncthreads();
-    const uint32_t prefix = s_prefix;
-    for (int i = threadIdx.x; i < C; i += kSqThreads) {
-      const uint32_t k = keys[i];
-      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
-    }
-    __syncthreads();
-    if (threadIdx.x < 64) wave_find_bin256<false>(hist, s_need, shift, &s_prefix, &s_need);   // ascending: smallest
-    mask |= 255u << shift;
-    __syncthreads();
-  }
-  const uint32_t tau = s_prefix;      // key of the n_keep-th smallest cosine
-  const uint32_t need_eq = s_need;    // how many elements equal to tau are kept (lowest positions first)
-  // Ordered pass: thread t owns the contiguous positions [t*ipt, (t+1)*ipt).
-  const int ipt = (C + kSqThreads - 1) / kSqThreads;
-  const int lo = threadIdx.x * ipt;
-  const int hi = min(lo + ipt, C);
-  uint32_t c_eq = 0;
-  for (int i = lo; i < hi; ++i) c_eq += (keys[i] == tau);
-  uint32_t tot_eq;
-  uint32_t eq_rank = block_excl_scan<kSqThreads>(c_eq, wsum, &tot_eq);
-  for (int i = lo; i < hi; ++i) {
-    const uint32_t k = keys[i];
-    bool take = k < tau;
-    if (k == tau) {
-      take = eq_rank < need_eq;
-      ++eq_rank;
-    }
-    if (take) {
-      const uint32_t slot = atomicAdd(&n_lt, 1u);   // slot order is irrelevant: ranks are recomputed below
-      if (slot < 128u) {
-        sel_key[slot] = k;
-        sel_idx[slot] = (uint32_t)i;
+  __shared__ uint32_t s_prefix, s_need, n_sel;
+  __shared__ uint32_t wsum[NW + 1];
+  __shared__ uint32_t sel_key[kMaxKeep];
+  __shared__ uint32_t sel_idx[kMaxKeep];
+  __shared__ int32_t idx_sh[kMaxGroup][kMaxKeep];
+  const int kv = blockIdx.x, b = blockIdx.y;
+  const int C = dm.C, g = dm.g;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+
+  for (int j = 0; j < g; ++j) {
+    const int h = kv * g + j;
+    if (C <= dm.n_ret) {   // nothing to drop: position order (Alg. 1 skips the sub-selection)
+      if (tid < n_keep) idx_sh[j][tid] = tid;
+    } else {
+      const float* cv = cosv + (size_t)(b * dm.n_q + h) * C;
+      for (int i = tid; i < C; i += kSelThreads) keys[i] = okey(cv[i]);
+      if (tid == 0) {
+        s_prefix = 0;
+        s_need = (uint32_t)n_keep;   // rank (1-based, ascending) of the cut element
+        n_sel = 0;
+      }
+      __syncthreads();
+      uint32_t mask = 0;
+      for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        const uint32_t prefix = s_prefix;
+        for (int i = tid; i < C; i += kSelThreads) {
+          const uint32_t k = keys[i];
+          if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid < 64) wave_find_bin256<false>(hist, s_need, shift, &s_prefix, &s_need);   // ascending: smallest
+        mask |= 255u << shift;
+        __syncthreads();
+      }
+      const uint32_t tau = s_prefix;      // key of the n_keep-th smallest cosine
+      const uint32_t need_eq = s_need;    // how many elements equal to tau are kept (lowest positions first)
+      // ordered pass: thread t owns the contiguous positions [t*ipt, (t+1)*ipt)
+      const int ipt = (C + kSelThreads - 1) / kSelThreads;
+      const int lo = min(tid * ipt, C), hi = min(lo + ipt, C);
+      uint32_t c_eq = 0;
+      for (int i = lo; i < hi; ++i) c_eq += (keys[i] == tau);
+      uint32_t tot_eq;
+      uint32_t eq_rank = block_excl_scan<kSelThreads>(c_eq, wsum, &tot_eq);
+      for (int i = lo; i < hi; ++i) {
+        const uint32_t k = keys[i];
+        bool take = k < tau;
+        if (k == tau) {
+          take = eq_rank < need_eq;
+          ++eq_rank;
+        }
+        if (take) {
+          const uint32_t slot = atomicAdd(&n_sel, 1u);   // slot order is irrelevant: ranks are recomputed below
+          if (slot < (uint32_t)kMaxKeep) {
+            sel_key[slot] = k;
+            sel_idx[slot] = (uint32_t)i;
+          }
+        }
+      }
+      __syncthreads();
+      if (tid < n_keep) {
+        const uint32_t k = sel_key[tid], id = sel_idx[tid];
+        int rank = 0;
+        for (int jj = 0; jj < n_keep; ++jj) {
+          const uint32_t kj = sel_key[jj], ij = sel_idx[jj];
+          rank += (kj < k) || (kj == k && ij < id);
+        }
+        idx_sh[j][rank] = (int32_t)id;
       }
     }
+    __syncthreads();
+    if (tid < n_keep) q_idx[(size_t)(b * dm.n_q + h) * n_keep + tid] = idx_sh[j][tid];
   }
-  __syncthreads();
-  if ((int)threadIdx.x < n_keep) {
-    const uint32_t k = sel_key[threadIdx.x], id = sel_idx[threadIdx.x];
-    int rank = 0;
-    for (int j = 0; j < n_keep; ++j) {
-      const uint32_t kj = sel_key[j], ij = sel_idx[j];
-      rank += (kj < k) || (kj == k && ij < id);
-    }
-    q_idx[(size_t)(b * dm.n_q + h) * n_keep + rank] = (int32_t)id;
-  }
-}
 
-__global__ void sq_identity(Dims dm, int32_t* __restrict__ q_idx, int n_keep) {
-  const int h = blockIdx.x, b = blockIdx.y;
-  for (int i = threadIdx.x; i < n_keep; i += blockDim.x) q_idx[(size_t)(b * dm.n_q + h) * n_keep + i] = i;
-}
-
-// ---------------------------------------------------------------------------------------------
-// One wave per (r, kv, b): lanes own D/64 consecutive elements each.
-template <typename T, int D>
-__global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, const int32_t* __restrict__ q_idx,
-                                             float* __restrict__ qbar, int n_keep) {
-  constexpr int EPL = D / 64;
-  const int r = blockIdx.x, kv = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x;
-  float acc[EPL];
+  // -- group mean of unit retained queries: wave w takes rows w, w + NW, ...; all rows of a step are requested
+  //    before any is used.  Heads are accumulated in ascending order.
+  for (int r = w; r < n_keep; r += NW) {
+    float acc[EPL];
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-  for (int j = 0; j < dm.g; ++j) {
-    const int h = kv * dm.g + j;
-    const int tok = q_idx[(size_t)(b * dm.n_q + h) * n_keep + r];
-    const T* row = q + b * dm.qs[0] + h * dm.qs[1] + tok * dm.qs[2];
-    float v[EPL];
-    float ss = 0.f;
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    for (int j0 = 0; j0 < g; j0 += 4) {
+      float v[4][EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      v[e] = Elem<T>::load1(row + lane * EPL + e);
-      ss += v[e] * v[e];
+      for (int jj = 0; jj < 4; ++jj) {
+        const int j = min(j0 + jj, g - 1);
+        const T* row = q + b * dm.qs[0] + (size_t)(kv * g + j) * dm.qs[1] + (size_t)idx_sh[j][r] * dm.qs[2];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) v[jj][e] = Elem<T>::load1(row + lane * EPL + e);
+      }
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) ss += v[jj][e] * v[jj][e];
+        ss = group_sum<64>(ss);
+        const float nrm = fmaxf(sqrtf(ss), kNormEps);
+        if (j0 + jj < g) {   // wave-uniform
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[e] += v[jj][e] / nrm;
+        }
+      }
     }
-    ss = group_sum<64>(ss);
-    const float nrm = fmaxf(sqrtf(ss), kNormEps);
+    float* out = qbar + ((size_t)(b * dm.n_kv + kv) * n_keep + r) * D;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] += v[e] / nrm;
+    for (int e = 0; e < EPL; ++e) out[lane * EPL + e] = acc[e] / (float)g;
   }
-  float* out = qbar + ((size_t)(b * dm.n_kv + kv) * n_keep + r) * D;
-#pragma unroll
-  for (int e = 0; e < EPL; ++e) out[lane * EPL + e] = acc[e] / (float)dm.g;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -210,17 +236,16 @@ static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, fl
                                float* ws_cos, hipStream_t st) {
   const int n_keep = dm.n_ret < dm.C ? dm.n_ret : dm.C;
   const T* qp = static_cast<const T*>(q);
+  size_t lds = 4;
   if (dm.C > dm.n_ret) {
     const int n_tiles = (dm.C + kSqTile - 1) / kSqTile;
     dim3 grid(n_tiles, dm.n_q, dm.b);
     hipLaunchKernelGGL((sq_partial_sums<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, n_tiles);
     hipLaunchKernelGGL((sq_cosine<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, ws_cos, n_tiles);
-    hipLaunchKernelGGL(sq_select, dim3(dm.n_q, dm.b), dim3(kSqThreads), (size_t)dm.C * sizeof(uint32_t), st, dm,
-                       ws_cos, q_idx, n_keep);
-  } else {
-    hipLaunchKernelGGL(sq_identity, dim3(dm.n_q, dm.b), dim3(64), 0, st, dm, q_idx, n_keep);
+    lds = (size_t)dm.C * sizeof(uint32_t);
   }
-  hipLaunchKernelGGL((sq_qbar<T, D>), dim3(n_keep, dm.n_kv, dm.b), dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
+  hipLaunchKernelGGL((sq_select_qbar<T, D>), dim3(dm.n_kv, dm.b), dim3(kSelThreads), lds, st, dm, qp, ws_cos, q_idx,
+                     qbar, n_keep);
   return hipGetLastError();
 }
 

@@ -24,69 +24,110 @@ __device__ __forceinline__ int radix_shift(int pass) { return pass == 0 ? 21 : (
 __device__ __forceinline__ uint32_t radix_bins(int pass) { return pass == 2 ? 1024u : 2048u; }
 
 // ---------------------------------------------------------------------------------------------
-// Single-block path.
+// Single-block path.  Thread t keeps scores t*IPT .. t*IPT+IPT-1 in registers as order-preserving keys.
+// The radix select skips the leading bits that all keys share (scores of one head usually sit in a narrow
+// range, which would otherwise pile every key into one or two histogram bins of the first passes).
+template <int IPT>
 __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float* __restrict__ scores,
                                                            const int32_t* __restrict__ kv_lens,
                                                            const int32_t* __restrict__ budgets,
                                                            int32_t* __restrict__ k_idx, int32_t* __restrict__ k_cnt) {
-  extern __shared__ uint32_t keys[];   // [T_max]
   __shared__ uint32_t hist[256];
   __shared__ uint32_t s_prefix, s_need;
   __shared__ uint32_t wsum[kSmallThreads / 64 + 1];
+  __shared__ uint32_t wmin[kSmallThreads / 64], wmax[kSmallThreads / 64];
   const int kv = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int T = max(0, min(kv_lens[b], dm.T_max));
   const int B = max(0, min(min(budgets[b], T), dm.B_max));
   int32_t* out = k_idx + (size_t)(b * dm.n_kv + kv) * dm.B_max;
-  if (threadIdx.x == 0) k_cnt[b * dm.n_kv + kv] = B;
+  if (tid == 0) k_cnt[b * dm.n_kv + kv] = B;
   if (B == 0) return;
   if (B >= T) {
-    for (int i = threadIdx.x; i < T; i += kSmallThreads) out[i] = i;
+    for (int i = tid; i < T; i += kSmallThreads) out[i] = i;
     return;
   }
   const float* sc = scores + (size_t)(b * dm.n_kv + kv) * dm.T_max;
-  for (int i = threadIdx.x; i < T; i += kSmallThreads) keys[i] = okey(sc[i]);
-  if (threadIdx.x == 0) {
-    s_prefix = 0;
+  const int lo = tid * IPT;
+  uint32_t key[IPT];
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    const int t = lo + j;
+    // padding key 0 sorts below the image of every real score, so it is never selected (B < T)
+    key[j] = t < T ? okey(sc[t]) : 0u;
+    if (t < T) {
+      kmin = min(kmin, key[j]);
+      kmax = max(kmax, key[j]);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+  }
+  if (lane == 0) {
+    wmin[w] = kmin;
+    wmax[w] = kmax;
+  }
+  __syncthreads();
+  kmin = wmin[0];
+  kmax = wmax[0];
+#pragma unroll
+  for (int i = 1; i < kSmallThreads / 64; ++i) {
+    kmin = min(kmin, wmin[i]);
+    kmax = max(kmax, wmax[i]);
+  }
+  const uint32_t diff = kmin ^ kmax;
+  int hi = diff ? 32 - __clz(diff) : 0;                       // keys agree on all bits >= hi
+  uint32_t mask = hi >= 32 ? 0u : ~((hi == 0) ? 0u : ((1u << hi) - 1u));   // decided bits
+  if (tid == 0) {
+    s_prefix = kmax & mask;
     s_need = (uint32_t)B;   // rank (1-based, descending) of the cut element
   }
   __syncthreads();
-  uint32_t mask = 0;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+  while (hi > 0) {
+    const int lo_bit = max(hi - 8, 0);
+    const uint32_t dmask = (1u << (hi - lo_bit)) - 1u;
+    if (tid < 256) hist[tid] = 0;
     __syncthreads();
     const uint32_t prefix = s_prefix;
-    for (int i = threadIdx.x; i < T; i += kSmallThreads) {
-      const uint32_t k = keys[i];
-      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const uint32_t k = key[j];
+      if (lo + j < T && (k & mask) == prefix) atomicAdd(&hist[(k >> lo_bit) & dmask], 1u);
     }
     __syncthreads();
-    if (threadIdx.x < 64) wave_find_bin256<true>(hist, s_need, shift, &s_prefix, &s_need);   // descending: B largest
-    mask |= 255u << shift;
+    if (tid < 64) wave_find_bin256<true>(hist, s_need, lo_bit, &s_prefix, &s_need);   // descending: B largest
+    mask |= dmask << lo_bit;
+    hi = lo_bit;
     __syncthreads();
   }
   const uint32_t tau = s_prefix, need_eq = s_need;
-  const int ipt = (T + kSmallThreads - 1) / kSmallThreads;
-  const int lo = min(threadIdx.x * ipt, (unsigned)T), hi = min(lo + ipt, T);
   uint32_t c_gt = 0, c_eq = 0;
-  for (int i = lo; i < hi; ++i) {
-    const uint32_t k = keys[i];
-    c_gt += (k > tau);
-    c_eq += (k == tau);
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    const bool in = lo + j < T;
+    c_gt += in && (key[j] > tau);
+    c_eq += in && (key[j] == tau);
   }
   uint32_t tot;
   uint32_t p_gt = block_excl_scan<kSmallThreads>(c_gt, wsum, &tot);
   uint32_t p_eq = block_excl_scan<kSmallThreads>(c_eq, wsum, &tot);
   uint32_t pos = p_gt + min(p_eq, need_eq);
-  for (int i = lo; i < hi; ++i) {
-    const uint32_t k = keys[i];
-    bool take = k > tau;
-    if (k == tau) {
-      take = p_eq < need_eq;
-      ++p_eq;
-    }
-    if (take) {
-      if (pos < (uint32_t)B) out[pos] = i;   // guard: a malformed score array cannot push writes past the budget
-      ++pos;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    if (lo + j < T) {
+      const uint32_t k = key[j];
+      bool take = k > tau;
+      if (k == tau) {
+        take = p_eq < need_eq;
+        ++p_eq;
+      }
+      if (take) {
+        if (pos < (uint32_t)B) out[pos] = lo + j;   // guard: a malformed score array cannot push writes past the budget
+        ++pos;
+      }
     }
   }
 }
@@ -283,16 +324,19 @@ size_t topk_ws_words(const Dims& dm) {
 hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* kv_lens, const int32_t* budgets,
                             int32_t* k_idx, int32_t* k_cnt, uint32_t* ws, hipStream_t st) {
   if (dm.T_max <= kSmallMax) {
-    const size_t lds = (size_t)(dm.T_max > 0 ? dm.T_max : 1) * sizeof(uint32_t);
-    static bool attr_done = false;
-    if (!attr_done) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_small),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kSmallMax * (int)sizeof(uint32_t));
-      if (e != hipSuccess) return e;
-      attr_done = true;
+    const dim3 grid(dm.n_kv, dm.b), block(kSmallThreads);
+    const int ipt = (dm.T_max + kSmallThreads - 1) / kSmallThreads;
+    if (ipt <= 1) {
+      hipLaunchKernelGGL((topk_small<1>), grid, block, 0, st, dm, scores, kv_lens, budgets, k_idx, k_cnt);
+    } else if (ipt <= 2) {
+      hipLaunchKernelGGL((topk_small<2>), grid, block, 0, st, dm, scores, kv_lens, budgets, k_idx, k_cnt);
+    } else if (ipt <= 4) {
+      hipLaunchKernelGGL((topk_small<4>), grid, block, 0, st, dm, scores, kv_lens, budgets, k_idx, k_cnt);
+    } else if (ipt <= 8) {
+      hipLaunchKernelGGL((topk_small<8>), grid, block, 0, st, dm, scores, kv_lens, budgets, k_idx, k_cnt);
+    } else {
+      hipLaunchKernelGGL((topk_small<16>), grid, block, 0, st, dm, scores, kv_lens, budgets, k_idx, k_cnt);
     }
-    hipLaunchKernelGGL(topk_small, dim3(dm.n_kv, dm.b), dim3(kSmallThreads), lds, st, dm, scores, kv_lens, budgets,
-                       k_idx, k_cnt);
     return hipGetLastError();
   }
   const int n_tiles = lg_tiles(dm);

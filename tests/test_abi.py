@@ -81,6 +81,7 @@ def test_workspace_query_and_status_strings(pk):
     (dict(dtype=7), 2),
     (dict(n_retain=129), 2),
     (dict(chunk_len=8193), 2),
+    (dict(n_q_heads=34, n_kv_heads=2), 2),           # more than 16 q-heads per KV head
 ])
 def test_bad_shapes_are_rejected(pk, kw, code):
     st, _ = _ws_status(pk, _shape(pk, **kw))

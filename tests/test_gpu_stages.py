@@ -34,6 +34,9 @@ SELECT_CASES = [
     dict(dtype="bf16", n_q=4, n_kv=1, d=128, chunk=24, n_retain=32),      # C <= N_Q: identity
     dict(dtype="bf16", n_q=2, n_kv=2, d=128, chunk=1, n_retain=16),       # single query (decode-like)
     dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=2048, n_retain=128, batch=2),
+    dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=2500, n_retain=100),                 # multi-block path
+    dict(dtype="f32", n_q=2, n_kv=1, d=64, chunk=3000, n_retain=7),
+    dict(dtype="bf16", n_q=16, n_kv=1, d=64, chunk=300, n_retain=128),                  # group of 16
 ]
 
 
