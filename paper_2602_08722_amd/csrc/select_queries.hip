@@ -5,9 +5,10 @@
 //   sq_partial_sums : per (b, q-head, token tile) column sums of Q                     -> ws.part
 //   sq_cosine       : per (b, q-head, token tile) mean query from the partials (fixed order, so the
 //                     result is bit-reproducible), then CosSim(q_i, M_Q) for the tile   -> ws.cos
-//   sq_select_qbar  : per (b, KV head) the N' lowest cosines of each head of the group in rank order
-//                     (LDS radix select + rank by counting) -> q_idx, then the group mean of the
-//                     unit-normalised retained queries                                  -> qbar
+//   sq_select       : per (b, q-head) the N' lowest cosines in rank order (radix select on register-held
+//                     keys + rank by counting)                                          -> q_idx
+//   sq_qbar         : per (b, KV head, r) unit-normalise the r-th retained query of each head of the
+//                     group and average                                                 -> qbar
 #include "common.hip.h"
 #include "kernels.h"
 
@@ -104,130 +105,147 @@ __global__ __launch_bounds__(kSqThreads) void sq_cosine(Dims dm, const T* __rest
 }
 
 // ---------------------------------------------------------------------------------------------
-// One 1024-thread block per (b, KV head): for each q-head of the group, the N' lowest cosines in rank
-// order (LDS radix select, 8 bits per pass, ties to the lower position; then rank by counting), and, with
-// the group's index lists still in LDS, the group mean of the unit-normalised retained queries.
-// Dynamic LDS: C uint32 keys.
-constexpr int kSelThreads = 1024;
-constexpr int kMaxGroup = 16;
+// One block per (b, q-head): the N' lowest cosines in rank order.  Thread t keeps cosines t*IPT .. t*IPT+IPT-1
+// in registers as order-preserving keys; LDS radix select (8 bits per pass, ties to the lower position),
+// then the rank of every retained query among the retained ones by counting, spread over the whole block.
 constexpr int kMaxKeep = 128;
 
-template <typename T, int D>
-__global__ __launch_bounds__(kSelThreads) void sq_select_qbar(Dims dm, const T* __restrict__ q,
-                                                             const float* __restrict__ cosv,
-                                                             int32_t* __restrict__ q_idx, float* __restrict__ qbar,
-                                                             int n_keep) {
-  constexpr int NW = kSelThreads / 64;
-  constexpr int EPL = D / 64;
-  extern __shared__ uint32_t keys[];          // [C]
+template <int IPT>
+__global__ __launch_bounds__(kSqThreads) void sq_select(Dims dm, const float* __restrict__ cosv,
+                                                       int32_t* __restrict__ q_idx, int n_keep) {
   __shared__ uint32_t hist[256];
   __shared__ uint32_t s_prefix, s_need, n_sel;
-  __shared__ uint32_t wsum[NW + 1];
+  __shared__ uint32_t wsum[kSqThreads / 64 + 1];
   __shared__ uint32_t sel_key[kMaxKeep];
   __shared__ uint32_t sel_idx[kMaxKeep];
-  __shared__ int32_t idx_sh[kMaxGroup][kMaxKeep];
-  const int kv = blockIdx.x, b = blockIdx.y;
-  const int C = dm.C, g = dm.g;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-
-  for (int j = 0; j < g; ++j) {
-    const int h = kv * g + j;
-    if (C <= dm.n_ret) {   // nothing to drop: position order (Alg. 1 skips the sub-selection)
-      if (tid < n_keep) idx_sh[j][tid] = tid;
-    } else {
-      const float* cv = cosv + (size_t)(b * dm.n_q + h) * C;
-      for (int i = tid; i < C; i += kSelThreads) keys[i] = okey(cv[i]);
-      if (tid == 0) {
-        s_prefix = 0;
-        s_need = (uint32_t)n_keep;   // rank (1-based, ascending) of the cut element
-        n_sel = 0;
-      }
-      __syncthreads();
-      uint32_t mask = 0;
-      for (int shift = 24; shift >= 0; shift -= 8) {
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
-        const uint32_t prefix = s_prefix;
-        for (int i = tid; i < C; i += kSelThreads) {
-          const uint32_t k = keys[i];
-          if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (tid < 64) wave_find_bin256<false>(hist, s_need, shift, &s_prefix, &s_need);   // ascending: smallest
-        mask |= 255u << shift;
-        __syncthreads();
-      }
-      const uint32_t tau = s_prefix;      // key of the n_keep-th smallest cosine
-      const uint32_t need_eq = s_need;    // how many elements equal to tau are kept (lowest positions first)
-      // ordered pass: thread t owns the contiguous positions [t*ipt, (t+1)*ipt)
-      const int ipt = (C + kSelThreads - 1) / kSelThreads;
-      const int lo = min(tid * ipt, C), hi = min(lo + ipt, C);
-      uint32_t c_eq = 0;
-      for (int i = lo; i < hi; ++i) c_eq += (keys[i] == tau);
-      uint32_t tot_eq;
-      uint32_t eq_rank = block_excl_scan<kSelThreads>(c_eq, wsum, &tot_eq);
-      for (int i = lo; i < hi; ++i) {
-        const uint32_t k = keys[i];
-        bool take = k < tau;
-        if (k == tau) {
-          take = eq_rank < need_eq;
-          ++eq_rank;
-        }
-        if (take) {
-          const uint32_t slot = atomicAdd(&n_sel, 1u);   // slot order is irrelevant: ranks are recomputed below
-          if (slot < (uint32_t)kMaxKeep) {
-            sel_key[slot] = k;
-            sel_idx[slot] = (uint32_t)i;
-          }
-        }
-      }
-      __syncthreads();
-      if (tid < n_keep) {
-        const uint32_t k = sel_key[tid], id = sel_idx[tid];
-        int rank = 0;
-        for (int jj = 0; jj < n_keep; ++jj) {
-          const uint32_t kj = sel_key[jj], ij = sel_idx[jj];
-          rank += (kj < k) || (kj == k && ij < id);
-        }
-        idx_sh[j][rank] = (int32_t)id;
-      }
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int C = dm.C;
+  const int tid = threadIdx.x;
+  const float* cv = cosv + (size_t)(b * dm.n_q + h) * C;
+  const int lo = tid * IPT;
+  uint32_t key[IPT];
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) key[j] = lo + j < C ? okey(cv[lo + j]) : 0xFFFFFFFFu;
+  if (tid == 0) {
+    s_prefix = 0;
+    s_need = (uint32_t)n_keep;   // rank (1-based, ascending) of the cut element
+    n_sel = 0;
+  }
+  uint32_t mask = 0;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    hist[tid] = 0;   // kSqThreads == 256 bins
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const uint32_t k = key[j];
+      if (lo + j < C && (k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
     }
     __syncthreads();
-    if (tid < n_keep) q_idx[(size_t)(b * dm.n_q + h) * n_keep + tid] = idx_sh[j][tid];
+    if (tid < 64) wave_find_bin256<false>(hist, s_need, shift, &s_prefix, &s_need);   // ascending: smallest
+    mask |= 255u << shift;
+    __syncthreads();
   }
-
-  // -- group mean of unit retained queries: wave w takes rows w, w + NW, ...; all rows of a step are requested
-  //    before any is used.  Heads are accumulated in ascending order.
-  for (int r = w; r < n_keep; r += NW) {
-    float acc[EPL];
+  const uint32_t tau = s_prefix;      // key of the n_keep-th smallest cosine
+  const uint32_t need_eq = s_need;    // how many elements equal to tau are kept (lowest positions first)
+  uint32_t c_eq = 0;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-    for (int j0 = 0; j0 < g; j0 += 4) {
-      float v[4][EPL];
+  for (int j = 0; j < IPT; ++j) c_eq += (lo + j < C) && (key[j] == tau);
+  uint32_t tot_eq;
+  uint32_t eq_rank = block_excl_scan<kSqThreads>(c_eq, wsum, &tot_eq);
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int j = min(j0 + jj, g - 1);
-        const T* row = q + b * dm.qs[0] + (size_t)(kv * g + j) * dm.qs[1] + (size_t)idx_sh[j][r] * dm.qs[2];
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) v[jj][e] = Elem<T>::load1(row + lane * EPL + e);
+  for (int j = 0; j < IPT; ++j) {
+    if (lo + j < C) {
+      const uint32_t k = key[j];
+      bool take = k < tau;
+      if (k == tau) {
+        take = eq_rank < need_eq;
+        ++eq_rank;
       }
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        float ss = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) ss += v[jj][e] * v[jj][e];
-        ss = group_sum<64>(ss);
-        const float nrm = fmaxf(sqrtf(ss), kNormEps);
-        if (j0 + jj < g) {   // wave-uniform
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) acc[e] += v[jj][e] / nrm;
+      if (take) {
+        const uint32_t slot = atomicAdd(&n_sel, 1u);   // slot order is irrelevant: ranks are computed below
+        if (slot < (uint32_t)kMaxKeep) {
+          sel_key[slot] = k;
+          sel_idx[slot] = (uint32_t)(lo + j);
         }
       }
     }
-    float* out = qbar + ((size_t)(b * dm.n_kv + kv) * n_keep + r) * D;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) out[lane * EPL + e] = acc[e] / (float)g;
   }
+  __syncthreads();
+  // rank by counting: P consecutive lanes share one retained query and split the comparisons
+  int nk2 = 1;
+  while (nk2 < n_keep) nk2 <<= 1;
+  const int P = kSqThreads / nk2;          // 2 .. 256, a power of two
+  const int e = tid / P, part = tid % P;
+  int rank = 0;
+  if (e < n_keep) {
+    const uint32_t k = sel_key[e], id = sel_idx[e];
+    for (int jj = part; jj < n_keep; jj += P) {
+      const uint32_t kj = sel_key[jj], ij = sel_idx[jj];
+      rank += (kj < k) || (kj == k && ij < id);
+    }
+  }
+  for (int o = 1; o < P && o < 64; o <<= 1) rank += __shfl_xor(rank, o, kWave);
+  if (P > 64) {   // n_keep < 4: the lanes of one query span waves; let lane 0 of each wave add through LDS
+    __syncthreads();
+    if ((tid & 63) == 0) wsum[tid >> 6] = (uint32_t)rank;
+    __syncthreads();
+    rank = 0;
+    const int w0 = (e * P) >> 6;
+    for (int i = 0; i < P / 64; ++i) rank += (int)wsum[w0 + i];
+  }
+  if (e < n_keep && part == 0) q_idx[(size_t)(b * dm.n_q + h) * n_keep + rank] = (int32_t)sel_idx[e];
+}
+
+__global__ void sq_identity(Dims dm, int32_t* __restrict__ q_idx, int n_keep) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  for (int i = threadIdx.x; i < n_keep; i += blockDim.x) q_idx[(size_t)(b * dm.n_q + h) * n_keep + i] = i;
+}
+
+// ---------------------------------------------------------------------------------------------
+// One wave per (r, kv, b): lanes own D/64 consecutive elements each.  The group's rows are all requested before
+// any is used, so the kernel pays one index latency and one row latency, not g of each.
+constexpr int kGroupUnroll = 8;
+template <typename T, int D>
+__global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, const int32_t* __restrict__ q_idx,
+                                             float* __restrict__ qbar, int n_keep) {
+  constexpr int EPL = D / 64;
+  const int r = blockIdx.x, kv = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x;
+  float acc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+  for (int j0 = 0; j0 < dm.g; j0 += kGroupUnroll) {
+    int tok[kGroupUnroll];
+#pragma unroll
+    for (int jj = 0; jj < kGroupUnroll; ++jj) {
+      const int j = min(j0 + jj, dm.g - 1);
+      tok[jj] = q_idx[(size_t)(b * dm.n_q + kv * dm.g + j) * n_keep + r];
+    }
+    float v[kGroupUnroll][EPL];
+#pragma unroll
+    for (int jj = 0; jj < kGroupUnroll; ++jj) {
+      const int j = min(j0 + jj, dm.g - 1);
+      const T* row = q + b * dm.qs[0] + (size_t)(kv * dm.g + j) * dm.qs[1] + (size_t)tok[jj] * dm.qs[2];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) v[jj][e] = Elem<T>::load1(row + lane * EPL + e);
+    }
+#pragma unroll
+    for (int jj = 0; jj < kGroupUnroll; ++jj) {
+      float ss = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) ss += v[jj][e] * v[jj][e];
+      ss = group_sum<64>(ss);
+      const float nrm = fmaxf(sqrtf(ss), kNormEps);
+      if (j0 + jj < dm.g) {   // wave-uniform; heads are accumulated in ascending order
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += v[jj][e] / nrm;
+      }
+    }
+  }
+  float* out = qbar + ((size_t)(b * dm.n_kv + kv) * n_keep + r) * D;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) out[lane * EPL + e] = acc[e] / (float)dm.g;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -236,16 +254,26 @@ static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, fl
                                float* ws_cos, hipStream_t st) {
   const int n_keep = dm.n_ret < dm.C ? dm.n_ret : dm.C;
   const T* qp = static_cast<const T*>(q);
-  size_t lds = 4;
   if (dm.C > dm.n_ret) {
     const int n_tiles = (dm.C + kSqTile - 1) / kSqTile;
     dim3 grid(n_tiles, dm.n_q, dm.b);
     hipLaunchKernelGGL((sq_partial_sums<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, n_tiles);
     hipLaunchKernelGGL((sq_cosine<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, ws_cos, n_tiles);
-    lds = (size_t)dm.C * sizeof(uint32_t);
+    const dim3 sgrid(dm.n_q, dm.b), sblock(kSqThreads);
+    const int ipt = (dm.C + kSqThreads - 1) / kSqThreads;
+    if (ipt <= 4) {
+      hipLaunchKernelGGL((sq_select<4>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+    } else if (ipt <= 8) {
+      hipLaunchKernelGGL((sq_select<8>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+    } else if (ipt <= 16) {
+      hipLaunchKernelGGL((sq_select<16>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+    } else {
+      hipLaunchKernelGGL((sq_select<32>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+    }
+  } else {
+    hipLaunchKernelGGL(sq_identity, dim3(dm.n_q, dm.b), dim3(64), 0, st, dm, q_idx, n_keep);
   }
-  hipLaunchKernelGGL((sq_select_qbar<T, D>), dim3(dm.n_kv, dm.b), dim3(kSelThreads), lds, st, dm, qp, ws_cos, q_idx,
-                     qbar, n_keep);
+  hipLaunchKernelGGL((sq_qbar<T, D>), dim3(n_keep, dm.n_kv, dm.b), dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
   return hipGetLastError();
 }
 
