@@ -24,6 +24,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
+# `bench.py --profile-stage sparse_attn`, scaled by the same counters' reading for a 1 GiB device copy
+# (profiles/attn_bf16_c2_hbm_traffic.txt).  None where it has not been measured.
+MEASURED_TRAFFIC_BYTES = {"c2": (16410 + 8320) * 1024}
+
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_VALU_PEAK_TFLOPS = 157.3
@@ -37,6 +42,10 @@ def _parse():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate-mib", type=int, default=640, help="total MiB of distinct K/V copies to rotate over")
+    ap.add_argument("--profile-stage", default=None,
+                    choices=["select_queries", "score_keys", "topk_keys", "sparse_attn", "dense_attn", "copy"],
+                    help="run only this stage --steps times (for rocprofv3 counter passes) and print a short JSON; "
+                         "'copy' runs a plain device copy of known size, used to calibrate the HBM byte counters")
     return ap.parse_args()
 
 
@@ -117,6 +126,26 @@ def main():
         bufs[i % n_copies].dense_attn()
 
     K, W = args.steps, args.warmup
+    if args.profile_stage is not None:
+        if args.profile_stage == "copy":
+            n = 256 << 20   # 1 GiB of float32 read + 1 GiB written per copy
+            src = torch.ones(n, dtype=torch.float32, device=dev)
+            dst = torch.empty_like(src)
+            for _ in range(K):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            print(json.dumps({"profile_stage": "copy", "steps": K, "bytes_read_per_step": 4 * n,
+                              "bytes_written_per_step": 4 * n}))
+            return
+        for i in range(n_copies):   # every buffer set gets valid intermediates
+            step(i)
+        torch.cuda.synchronize()
+        for i in range(K):
+            getattr(bufs[i % n_copies], args.profile_stage)()
+        torch.cuda.synchronize()
+        print(json.dumps({"profile_stage": args.profile_stage, "steps": K, "workload": w.name,
+                          "algorithmic": _algorithmic(w)}))
+        return
     for i in range(W):
         step(i)
     torch.cuda.synchronize()
@@ -170,7 +199,8 @@ def main():
     if w.dtype == "bf16":
         roofline = {"kernel": "attn_bf16 (quoka_sparse_attn)", "bound": "mfma", "achieved": attn_tflops,
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": None}
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "algorithmic_bytes": alg["sparse_bytes"],
+                    "algorithmic_flops": alg["sparse_flops"], "kernel_us": attn_us}
     else:
         roofline = {"kernel": "attn_f32 (quoka_sparse_attn)", "bound": "alu", "achieved": attn_tflops,
                     "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / FP32_VALU_PEAK_TFLOPS,
