@@ -36,14 +36,20 @@ struct AttnCfg {
   static constexpr size_t kLdsBytes = 4 * kTileBytes;  // K and V, double buffered
 };
 
-template <int D>
-__global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) {
+// NSETS = 1: a block is 4 waves.  NSETS = 2: a block is 8 waves; waves 4-7 take the same 4 row blocks as waves 0-3
+// but every other KV tile (own LDS buffers, same barriers), and the two partial results are merged through LDS at
+// the end.  This puts two waves on every SIMD when the grid alone cannot (one row block per SIMD), so one wave's
+// softmax overlaps the other's MFMAs.
+template <int D, int NSETS>
+__global__ __launch_bounds__(kAtThreads * NSETS, 2) void attn_bf16(Dims dm, AttnArgs a) {
   using Cfg = AttnCfg<D>;
   constexpr int KS = Cfg::KS, LD = Cfg::LD, CG = Cfg::CG, RPI = Cfg::RPI, NLD = Cfg::NLD, DB = Cfg::DB;
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int kv = blockIdx.x, b = blockIdx.z;   // KV head fastest: one head's blocks share an XCD's L2
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x % kAtThreads, lane = tid & 63, w = tid >> 6;   // position inside the wave set
+  const int set = threadIdx.x / kAtThreads;
+  unsigned char* const smem_set = smem + (size_t)set * Cfg::kLdsBytes;
   const int li = lane & 31, hf = lane >> 5;
   const int C = dm.C, g = dm.g;
   const int ntt = (C + 31) / 32;
@@ -116,9 +122,9 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
     }                                                                                              \
   } while (0)
 
-  QUOKA_RESOLVE(0);
-  QUOKA_ISSUE(0);
-  QUOKA_RESOLVE(1);
+  QUOKA_RESOLVE(set);
+  if (set < n_tiles) QUOKA_ISSUE(set);
+  QUOKA_RESOLVE(set + NSETS);
 
   f32x16 o[DB];
 #pragma unroll
@@ -130,20 +136,26 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
   const float sl2 = 1.4426950408889634f / sqrtf((float)D);
   const int tok = tok0 + li;
 
-  for (int it = 0; it < n_tiles; ++it) {
-    uint16_t* kt = reinterpret_cast<uint16_t*>(smem + (size_t)(it & 1) * 2 * Cfg::kTileBytes);
+  const int n_steps = (n_tiles + NSETS - 1) / NSETS;
+  for (int j = 0; j < n_steps; ++j) {
+    const int it = j * NSETS + set;       // this wave set's tile of the step
+    const bool has_tile = it < n_tiles;
+    uint16_t* kt = reinterpret_cast<uint16_t*>(smem_set + (size_t)(j & 1) * 2 * Cfg::kTileBytes);
     uint16_t* vt = kt + kBN * LD;
+    if (has_tile) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int rl = r0 + RPI * i;
-      *reinterpret_cast<u32x4*>(kt + rl * LD + cg * 8) = RK[i];
-      *reinterpret_cast<u32x4*>(vt + rl * LD + cg * 8) = RV[i];
+      for (int i = 0; i < NLD; ++i) {
+        const int rl = r0 + RPI * i;
+        *reinterpret_cast<u32x4*>(kt + rl * LD + cg * 8) = RK[i];
+        *reinterpret_cast<u32x4*>(vt + rl * LD + cg * 8) = RV[i];
+      }
     }
     __syncthreads();   // tile `it` visible; every wave is past its reads of the other buffer's previous use
-    if (it + 1 < n_tiles) {
-      QUOKA_ISSUE(it + 1);
-      QUOKA_RESOLVE(it + 2);
+    if (it + NSETS < n_tiles) {
+      QUOKA_ISSUE(it + NSETS);
+      QUOKA_RESOLVE(it + 2 * NSETS);
     }
+    if (!has_tile) continue;
 
     const bool is_chunk = it >= n_ct;
     const int base = is_chunk ? (it - n_ct) * kBN : it * kBN;   // first key of the tile in its own numbering
@@ -242,6 +254,33 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
     }
   }
 
+  // ---- merge of the two wave sets (NSETS == 2): set 1 hands (m, l, O) to set 0 through LDS ------------------------
+  if constexpr (NSETS == 2) {
+    constexpr int REC = 2 + DB * 16;
+    float* mg = reinterpret_cast<float*>(smem) + (size_t)(w * 64 + lane) * REC;
+    __syncthreads();   // all tiles consumed: the tile buffers may be reused
+    if (set == 1) {
+      mg[0] = m_run;
+      mg[1] = l_run;
+#pragma unroll
+      for (int c = 0; c < DB; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mg[2 + c * 16 + v] = o[c][v];
+    }
+    __syncthreads();
+    if (set == 1) return;
+    const float m1 = mg[0], l1 = mg[1];
+    const float m_new = fmaxf(m_run, m1);
+    const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
+    const float a0 = __builtin_amdgcn_exp2f(m_run - m_fin), a1 = __builtin_amdgcn_exp2f(m1 - m_fin);
+    m_run = m_new;
+    l_run = a0 * l_run + a1 * l1;
+#pragma unroll
+    for (int c = 0; c < DB; ++c)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[c][v] = a0 * o[c][v] + a1 * mg[2 + c * 16 + v];
+  }
+
   // ---- epilogue -------------------------------------------------------------------------------
   const float l_tot = l_run + other_half(l_run);
   if (wave_on && tok < C) {
@@ -269,20 +308,31 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_bf16(Dims dm, AttnArgs a) 
 #undef QUOKA_RESOLVE
 #undef QUOKA_ISSUE
 
-template <int D>
-static hipError_t launch_d(const Dims& dm, const AttnArgs& a, hipStream_t st) {
+template <int D, int NSETS>
+static hipError_t launch_dn(const Dims& dm, const AttnArgs& a, int n_blocks_y, hipStream_t st) {
   using Cfg = AttnCfg<D>;
+  constexpr size_t lds = NSETS * Cfg::kLdsBytes;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16<D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16<D, NSETS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  const int nrb = dm.g * ((dm.C + 31) / 32);
-  dim3 grid(dm.n_kv, (nrb + 3) / 4, dm.b);
-  hipLaunchKernelGGL((attn_bf16<D>), grid, dim3(kAtThreads), Cfg::kLdsBytes, st, dm, a);
+  dim3 grid(dm.n_kv, n_blocks_y, dm.b);
+  hipLaunchKernelGGL((attn_bf16<D, NSETS>), grid, dim3(kAtThreads * NSETS), lds, st, dm, a);
   return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_d(const Dims& dm, const AttnArgs& a, hipStream_t st) {
+  constexpr int kComputeUnits = 256;   // MI355X
+  const int nrb = dm.g * ((dm.C + 31) / 32);
+  const int ny = (nrb + 3) / 4;
+  const long long blocks = (long long)dm.n_kv * ny * dm.b;
+  // fewer than two 4-wave blocks per compute unit: use 8-wave blocks that split the KV tiles between two wave sets
+  if (blocks < 2 * kComputeUnits) return launch_dn<D, 2>(dm, a, ny, st);
+  return launch_dn<D, 1>(dm, a, ny, st);
 }
 
 hipError_t launch_attn_bf16(const Dims& dm, const AttnArgs& a, hipStream_t st) {
