@@ -77,6 +77,24 @@ __device__ __forceinline__ float group_max(float x) {
   return x;
 }
 
+// Sum over each aligned group of 16 lanes (one DPP row) with four row rotations: plain VALU work, no LDS
+// crossbar traffic.  Every lane of the group gets the sum.
+__device__ __forceinline__ float row16_sum(float x) {
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x128, 0xF, 0xF, false));   // row_ror:8
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x124, 0xF, 0xF, false));   // row_ror:4
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x122, 0xF, 0xF, false));   // row_ror:2
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x121, 0xF, 0xF, false));   // row_ror:1
+  return x;
+}
+
+// Sum over the 64 lanes of a wave: DPP inside each 16-lane row, then two cross-row exchanges.
+__device__ __forceinline__ float wave64_sum(float x) {
+  x = row16_sum(x);
+  x += __shfl_xor(x, 16, kWave);
+  x += __shfl_xor(x, 32, kWave);
+  return x;
+}
+
 // Exchange between lane l and lane l^32 through v_permlane32_swap: returns the partner's value.
 __device__ __forceinline__ float other_half(float x) {
   const uint32_t u = __float_as_uint(x);

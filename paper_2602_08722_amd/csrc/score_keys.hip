@@ -114,7 +114,12 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
     for (int i = 0; i < NLD; ++i) {
       const int rl = r0 + RPI * i;
       *reinterpret_cast<u32x4*>(tl + rl * LD + cg * 8) = R[i];
-      const float ss = group_sum<CG>(sumsq_bf16x8(R[i]));
+      float ss = sumsq_bf16x8(R[i]);
+      if constexpr (CG == 16) {
+        ss = row16_sum(ss);   // a key row is exactly one 16-lane DPP row
+      } else {
+        ss = group_sum<CG>(ss);
+      }
       if (cg == 0) ssq[buf * kScTile + rl] = ss;
     }
     __syncthreads();

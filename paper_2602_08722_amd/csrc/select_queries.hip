@@ -95,8 +95,13 @@ __global__ __launch_bounds__(kSqThreads) void sq_cosine(Dims dm, const T* __rest
       dot += v[e] * m[e];
       qq += v[e] * v[e];
     }
-    dot = group_sum<CG>(dot);
-    qq = group_sum<CG>(qq);
+    if constexpr (CG == 16) {   // a query row is exactly one 16-lane DPP row
+      dot = row16_sum(dot);
+      qq = row16_sum(qq);
+    } else {
+      dot = group_sum<CG>(dot);
+      qq = group_sum<CG>(qq);
+    }
     if (cg == 0 && tok < dm.C) {
       const float qn = fmaxf(sqrtf(qq), kNormEps);
       cosv[(size_t)(b * dm.n_q + h) * dm.C + tok] = dot / (qn * mn) + 0.0f;
@@ -235,7 +240,7 @@ __global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, 
       float ss = 0.f;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) ss += v[jj][e] * v[jj][e];
-      ss = group_sum<64>(ss);
+      ss = wave64_sum(ss);
       const float nrm = fmaxf(sqrtf(ss), kNormEps);
       if (j0 + jj < dm.g) {   // wave-uniform; heads are accumulated in ascending order
 #pragma unroll
