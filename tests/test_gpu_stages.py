@@ -37,6 +37,9 @@ SELECT_CASES = [
     dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=2500, n_retain=100),                 # multi-block path
     dict(dtype="f32", n_q=2, n_kv=1, d=64, chunk=3000, n_retain=7),
     dict(dtype="bf16", n_q=16, n_kv=1, d=64, chunk=300, n_retain=128),                  # group of 16
+    dict(dtype="bf16", n_q=2, n_kv=1, d=128, chunk=8192, n_retain=128),                 # largest chunk, largest N_Q
+    dict(dtype="bf16", n_q=2, n_kv=2, d=128, chunk=5000, n_retain=1),                   # a single retained query
+    dict(dtype="bf16", n_q=2, n_kv=2, d=128, chunk=700, n_retain=3),
 ]
 
 
@@ -135,6 +138,10 @@ TOPK_CASES = [
     ([20000, 33000, 0, 17000], [2000, 33000, 5, 1], 33000, "normal"),
     ([131072], [8192], 131072, "normal"),
     ([131072], [8192], 131072, "const"),
+    ([16384], [16383], 16384, "normal"),                    # largest single-block size, budget T-1
+    ([16385], [1], 16385, "signed"),                        # smallest multi-block size
+    ([1], [1], 1, "normal"),
+    ([3, 1, 2], [2, 5, 1], 3, "ties"),
 ]
 
 
