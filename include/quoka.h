@@ -26,7 +26,8 @@
  *       QUOKA_EWORKSPACE   workspace smaller than quoka_workspace_bytes() says (or misaligned)
  *       QUOKA_EHIP         the HIP runtime refused a launch
  *   - Limits: n_retain <= 128, chunk_len <= 8192, max_kv_len < 2^24, max_budget <= max_kv_len,
- *     n_q_heads / n_kv_heads <= 16.
+ *     n_q_heads / n_kv_heads <= 16; the rows of one (batch, KV head) slice span less than 4 GiB
+ *     (max_kv_len * kv_stride[2] * element size < 2^32, likewise chunk_len * ck_stride[2]).
  *   - kv_lens[b] == 0 is legal (first chunk): nothing is selected and attention is plain causal
  *     attention over the chunk.  A budget >= kv_lens[b] selects the whole cache.
  *   - Inputs are assumed finite (no NaN/Inf).

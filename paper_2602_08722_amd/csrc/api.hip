@@ -41,6 +41,11 @@ quoka_status check_shape(const quoka_shape* s, Dims* dm) {
       if (st[i] < 0 || st[i] % 8 != 0) return QUOKA_EINVAL;
     if (st[2] < s->head_dim) return QUOKA_EINVAL;
   }
+  // kernels address the rows of one (batch, KV head) slice with 32-bit byte offsets
+  const int es = s->dtype == QUOKA_BF16 ? 2 : 4;
+  if ((unsigned long long)s->max_kv_len * (unsigned long long)s->kv_stride[2] * es >= (1ull << 32) ||
+      (unsigned long long)s->chunk_len * (unsigned long long)s->ck_stride[2] * es >= (1ull << 32))
+    return QUOKA_EUNSUPPORTED;
   dm->b = s->batch;
   dm->n_q = s->n_q_heads;
   dm->n_kv = s->n_kv_heads;
