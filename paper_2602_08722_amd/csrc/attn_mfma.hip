@@ -239,6 +239,7 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
         for (int v = 0; v < 16; ++v) o[c][v] *= alpha;
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+    __builtin_amdgcn_s_setprio(2);   // the wave feeding the matrix core goes first; its SIMD mate fills the gaps
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -272,6 +273,7 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
       }
     }
     l_run += psum;
+    __builtin_amdgcn_s_setprio(0);
   }
 
   // ---- merge of the two wave sets (NSETS == 2): set 1 hands (m, l, O) to set 0 through LDS ------------------------
