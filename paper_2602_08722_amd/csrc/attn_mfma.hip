@@ -4,9 +4,9 @@
 // never materialised) and the dense baseline of Eq. 2 (rows 0..kv_len).
 //
 // Work split: a wave owns a row block: 32 query rows of one q-head.  Row blocks of a KV head are numbered
-// (token tile, head-in-group), and a block's waves take half of their row blocks from the front of that list
-// and half from the back, so every block (and, with two waves per SIMD, every SIMD) gets the same mix of
-// short and long causal ranges.  All waves of a block share every staged K/V tile.
+// (token tile, head-in-group); a block takes half of its row blocks from the front of that list and half from
+// the back, so every block (and every SIMD, which hosts one wave of each kind) gets the same mix of short and
+// long causal ranges.  A block is two sets of four waves that share every staged K/V tile.
 //
 // MFMA operand plan (v_mfma_f32_32x32x16_bf16; a lane is (li = lane % 32, hf = lane / 32)):
 //   S^T[key, row] = K[key, :] . Q[row, :]      A = K tile rows from LDS, B = Q held in registers.
@@ -20,6 +20,11 @@
 //     pointing at key row0 + s/4, dims dim0 + 4*(s%4), lane L ends up with dim dim0 + L of keys
 //     row0 .. row0+3: a quarter of an MFMA A operand, with no register shuffling.
 //     Accumulator block c, register v of lane li holds O[row li, dim 32*c + 8*(v/4) + 4*hf + v%4].
+//
+// Schedule: the two wave sets run half a step apart.  While one set forms S = K Q^T of a tile (matrix core only)
+// the other runs softmax and P V (exponentials interleaved with MFMAs), then they swap.  A SIMD hosts one wave of
+// each set, so its matrix core always has one wave that only feeds it and one whose vector work fills the gaps.
+// Two barriers per step keep the halves aligned and protect the double-buffered LDS stages.
 #include "common.hip.h"
 #include "kernels.h"
 
@@ -30,50 +35,52 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef s16x4 __attribute__((address_space(3))) * tr_ptr;   // LDS address of one lane's 8 bytes of a transposing read
 
-constexpr int kBN = 64;   // keys per staged tile
+constexpr int kSetThreads = 256;   // four waves
+constexpr int kSub = 64;           // keys a wave set consumes per step
 
-// NW = waves per wave set (4 or 8); a block holds NSETS wave sets.
-template <int D, int NW>
+// SPLIT = false: the sets own different row blocks (8 per block) and both consume every 64-key tile.
+// SPLIT = true:  both sets own the same 4 row blocks; a staged tile has 128 keys, set s consumes keys 64*s..64*s+63,
+//                and the two partial results are merged through LDS at the end.  Used when 8 row blocks per block
+//                would leave compute units without a block.
+template <int D, bool SPLIT>
 struct AttnCfg {
-  static constexpr int kThreads = 64 * NW;
-  static constexpr int KS = D / 16;              // k-steps of the QK^T product
-  static constexpr int LD = D + 8;               // padded LDS row of the K tile (elements)
-  static constexpr int LDV = D + 32;             // V tile: rows 64 bytes apart modulo 256, so the 8 rows x 64 bytes
-                                                 // one transposing read touches fall on distinct banks per half wave
-  static constexpr int CG = D / 8;               // 16-byte chunks per row
-  static constexpr int RPI = kThreads / CG;    // rows per block-wide load
-  static constexpr int NLD = kBN / RPI;          // loads per thread per tile (per tensor)
-  static constexpr int DB = D / 32;              // dim blocks of the PV product
-  static constexpr size_t kKTileBytes = (size_t)kBN * LD * 2;
-  static constexpr size_t kStageBytes = kKTileBytes + (size_t)kBN * LDV * 2;   // one K tile and one V tile
+  static constexpr int KT = SPLIT ? 2 * kSub : kSub;  // keys per staged tile
+  static constexpr int KS = D / 16;                   // k-steps of the QK^T product
+  static constexpr int LD = D + 8;                    // padded LDS row of the K tile (elements)
+  static constexpr int LDV = D + 32;                  // V tile: rows 64 bytes apart modulo 256, so the 8 rows x 64 bytes
+                                                      // one transposing read touches fall on distinct banks per half wave
+  static constexpr int CG = D / 8;                    // 16-byte chunks per row
+  static constexpr int RPI = kSetThreads / CG;        // rows per set-wide load
+  static constexpr int NLD = KT / RPI;                // loads per thread per tile (set 0 loads K, set 1 loads V)
+  static constexpr int DB = D / 32;                   // dim blocks of the PV product
+  static constexpr int HW = SPLIT ? 2 : 4;            // front (= back) row blocks per block
+  static constexpr size_t kKTileBytes = (size_t)KT * LD * 2;
+  static constexpr size_t kStageBytes = kKTileBytes + (size_t)KT * LDV * 2;   // one K tile and one V tile
   static constexpr size_t kLdsBytes = 2 * kStageBytes;                          // double buffered
 };
 
-// NSETS = 1: one set of NW waves.  NSETS = 2 (NW = 4): waves 4-7 take the same 4 row blocks as waves 0-3 but every
-// other KV tile (own LDS buffers, same barriers), and the two partial results are merged through LDS at the end.
-// This puts two waves on every SIMD when the grid alone cannot.  The second set's waves are rotated by two
-// against the first's, so each SIMD hosts one front (short) and one back (long) row block.
-template <int D, int NW, int NSETS>
-__global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArgs a) {
-  using Cfg = AttnCfg<D, NW>;
-  constexpr int KS = Cfg::KS, LD = Cfg::LD, LDV = Cfg::LDV, CG = Cfg::CG, RPI = Cfg::RPI, NLD = Cfg::NLD, DB = Cfg::DB;
-  constexpr int kThreads = Cfg::kThreads, HW = NW / 2;
+template <int D, bool SPLIT>
+__global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArgs a) {
+  using Cfg = AttnCfg<D, SPLIT>;
+  constexpr int KT = Cfg::KT, KS = Cfg::KS, LD = Cfg::LD, LDV = Cfg::LDV, CG = Cfg::CG, RPI = Cfg::RPI, NLD = Cfg::NLD,
+                DB = Cfg::DB, HW = Cfg::HW;
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int kv = blockIdx.x, b = blockIdx.z;   // KV head fastest: one head's blocks share an XCD's L2
-  const int tid = threadIdx.x % kThreads, lane = tid & 63;                    // position inside the wave set
+  const int tid = threadIdx.x % kSetThreads, lane = tid & 63;                 // position inside the wave set
   // wave-uniform values are pinned to scalar registers so that everything derived from them (tile kind, base
   // pointers, branches) stays scalar too
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int set = NSETS == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x / kThreads);
-  unsigned char* const smem_set = smem + (size_t)set * Cfg::kLdsBytes;
+  const int set = __builtin_amdgcn_readfirstlane(threadIdx.x / kSetThreads);
   const int li = lane & 31, hf = lane >> 5;
   const int C = dm.C, g = dm.g;
   const int ntt = (C + 31) / 32;
   const int nrb = g * ntt;                       // row blocks of this KV head
   const int half = (nrb + 1) / 2;                // row blocks [0, half) are "front", [half, nrb) "back"
-  const int slot = NSETS == 1 ? w : (w + HW * set) % NW;   // slots [0, HW) front, [HW, NW) back
-  const bool back = slot >= HW;
+  // SPLIT: slots 0,1 front, 2,3 back, and set 1's waves are rotated by two so that each SIMD hosts a front and a back
+  // row block.  Otherwise set 0 is front, set 1 back.
+  const int slot = SPLIT ? (w + 2 * set) % 4 : w + 4 * set;
+  const bool back = SPLIT ? slot >= 2 : set == 1;
   const int kf = blockIdx.y * HW + slot % HW;
   const int x = back ? nrb - 1 - kf : kf;
   const bool wave_on = back ? (x >= half) : (x < half);
@@ -83,6 +90,7 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
   const int xb_hi = nrb - 1 - (int)blockIdx.y * HW;                                     // the block's last row block
   const int x_hi = xb_hi >= half ? xb_hi : min((int)blockIdx.y * HW + HW - 1, half - 1);
   const int c_end_blk = min((x_hi / g) * 32 + 32, C);   // chunk keys any wave of this block can see
+  const int sub = SPLIT ? set * kSub : 0;               // first key of this set's share of a staged tile
 
   const bool sparse = a.k_idx != nullptr;
   int n_cache;
@@ -92,32 +100,33 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
     n_cache = min(a.n_cache[b], dm.T_max);
   }
   n_cache = max(n_cache, 0);
-  const int n_ct = (n_cache + kBN - 1) / kBN;
-  const int n_tiles = n_ct + (c_end_blk + kBN - 1) / kBN;
+  const int n_ct = (n_cache + KT - 1) / KT;
+  const int n_tiles = n_ct + (c_end_blk + KT - 1) / KT;
 
   const uint16_t* qg = static_cast<const uint16_t*>(a.q);
-  // K and V of this (batch, KV head), as byte pointers: every row is addressed as base + 32-bit byte offset
-  // (the host checks that a head's rows span less than 4 GiB), which keeps the per-tile address arithmetic
-  // to one multiply-add per staged row.
-  const char* kcache = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.k_cache) + b * dm.kvs[0] + kv * dm.kvs[1]);
-  const char* vcache = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.v_cache) + b * dm.kvs[0] + kv * dm.kvs[1]);
-  const char* kchunk = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.k_chunk) + b * dm.cks[0] + kv * dm.cks[1]);
-  const char* vchunk = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.v_chunk) + b * dm.cks[0] + kv * dm.cks[1]);
+  // The tensor this set stages (set 0: K, set 1: V) for this (batch, KV head), as byte pointers: every row is
+  // addressed as base + 32-bit byte offset (the host checks that a head's rows span less than 4 GiB).
+  const void* cache_t = set == 0 ? a.k_cache : a.v_cache;
+  const void* chunk_t = set == 0 ? a.k_chunk : a.v_chunk;
+  const char* cache_base = reinterpret_cast<const char*>(static_cast<const uint16_t*>(cache_t) + b * dm.kvs[0] + kv * dm.kvs[1]);
+  const char* chunk_base = reinterpret_cast<const char*>(static_cast<const uint16_t*>(chunk_t) + b * dm.cks[0] + kv * dm.cks[1]);
   const char* kidx = sparse ? reinterpret_cast<const char*>(a.k_idx + (size_t)(b * dm.n_kv + kv) * dm.B_max) : nullptr;
   const uint32_t cache_row_bytes = (uint32_t)dm.kvs[2] * 2u, chunk_row_bytes = (uint32_t)dm.cks[2] * 2u;
+  const int ld_mine = set == 0 ? LD : LDV;                              // LDS row pitch of the tensor this set stages
+  const size_t stage_off_mine = set == 0 ? 0 : Cfg::kKTileBytes;      // its place inside a stage
 
   // Q operand: row tok0 + li, dims ks*16 + 8*hf .. +8
   bf16x8 qreg[KS];
   {
-    const int tok = min(tok0 + li, C - 1);
-    const uint16_t* qrow = qg + b * dm.qs[0] + h * dm.qs[1] + (size_t)tok * dm.qs[2] + 8 * hf;
+    const int tokq = min(tok0 + li, C - 1);
+    const uint16_t* qrow = qg + b * dm.qs[0] + h * dm.qs[1] + (size_t)tokq * dm.qs[2] + 8 * hf;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
   }
 
   const int cg = tid % CG, r0 = tid / CG;
   uint32_t rows[NLD];   // source rows of the tile to be issued next
-  u32x4 RK[NLD], RV[NLD];
+  u32x4 R[NLD];         // staging registers of the tile in flight
 
   // Source rows of a tile are resolved one tile ahead of the loads that use them, so the dependent
   // index -> row fetch of the gather never sits on the critical path: the fetched indices are first touched
@@ -128,7 +137,7 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
     const int it_ = (IT);                                                                          \
     if (it_ < n_tiles) {                                                                           \
       const bool cache_ = it_ < n_ct;                                                              \
-      const int base_ = cache_ ? it_ * kBN : (it_ - n_ct) * kBN;                                   \
+      const int base_ = cache_ ? it_ * KT : (it_ - n_ct) * KT;                                     \
       const int last_ = cache_ ? n_cache - 1 : C - 1;                                              \
       if (cache_ && sparse) {                                                                      \
         _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                                          \
@@ -144,19 +153,15 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
 #define QUOKA_ISSUE(IT)                                                                            \
   do {                                                                                             \
     const bool cache_ = (IT) < n_ct;                                                               \
-    const char* kb_ = cache_ ? kcache : kchunk;                                                    \
-    const char* vb_ = cache_ ? vcache : vchunk;                                                    \
+    const char* tb_ = cache_ ? cache_base : chunk_base;                                            \
     const uint32_t rb_ = cache_ ? cache_row_bytes : chunk_row_bytes;                               \
-    _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                                              \
-      const uint32_t off_ = rows[i] * rb_ + (uint32_t)cg * 16u;                                    \
-      RK[i] = *reinterpret_cast<const u32x4*>(kb_ + off_);                                         \
-      RV[i] = *reinterpret_cast<const u32x4*>(vb_ + off_);                                         \
-    }                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < NLD; ++i)                                                \
+      R[i] = *reinterpret_cast<const u32x4*>(tb_ + (rows[i] * rb_ + (uint32_t)cg * 16u));          \
   } while (0)
 
-  QUOKA_RESOLVE(set);
-  if (set < n_tiles) QUOKA_ISSUE(set);
-  QUOKA_RESOLVE(set + NSETS);
+  QUOKA_RESOLVE(0);
+  QUOKA_ISSUE(0);   // n_tiles >= 1: the chunk is never empty
+  QUOKA_RESOLVE(1);
 
   f32x16 o[DB];
 #pragma unroll
@@ -167,48 +172,41 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
   float l_run = 0.f;         // this half wave's share of the running row sum
   const float sl2 = 1.4426950408889634f / sqrtf((float)D);
   const int tok = tok0 + li;
+  f32x16 s[2];               // S^T of the tile between its two halves
 
-  const int n_steps = (n_tiles + NSETS - 1) / NSETS;
-  for (int j = 0; j < n_steps; ++j) {
-    const int it = j * NSETS + set;       // this wave set's tile of the step
-    const bool has_tile = it < n_tiles;
-    uint16_t* kt = reinterpret_cast<uint16_t*>(smem_set + (size_t)(j & 1) * Cfg::kStageBytes);
-    uint16_t* vt = kt + kBN * LD;
-    if (has_tile) {
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int rl = r0 + RPI * i;
-        *reinterpret_cast<u32x4*>(kt + rl * LD + cg * 8) = RK[i];
-        *reinterpret_cast<u32x4*>(vt + rl * LDV + cg * 8) = RV[i];
-      }
-    }
-    __syncthreads();   // tile `it` visible; every wave is past its reads of the other buffer's previous use
-    if (it + NSETS < n_tiles) {
-      QUOKA_ISSUE(it + NSETS);
-      QUOKA_RESOLVE(it + 2 * NSETS);
-    }
-    if (!has_tile) continue;
+  // first key (in the tile's own numbering: cache slot or chunk position) of this set's share of tile t
+  auto share_base = [&](int t) { return (t >= n_ct ? t - n_ct : t) * KT + sub; };
+  // whether this wave has anything visible in its share of tile t
+  auto computes = [&](int t) {
+    if (!wave_on || t < 0 || t >= n_tiles) return false;
+    const int base = share_base(t);
+    return t >= n_ct ? base <= tok0 + 31 : base < n_cache;
+  };
 
-    const bool is_chunk = it >= n_ct;
-    const int base = is_chunk ? (it - n_ct) * kBN : it * kBN;   // first key of the tile in its own numbering
-    if (!wave_on || (is_chunk && base > tok0 + 31)) continue;   // tile entirely in this wave's future
-
-    // ---- S^T = K Q^T --------------------------------------------------------------------------
-    f32x16 s[2];
+  // ---- first half of a tile: S^T = K Q^T ---------------------------------------------------------
+  auto qk = [&](int t) __attribute__((always_inline)) {
+    const uint16_t* kt = reinterpret_cast<const uint16_t*>(smem + (size_t)(t & 1) * Cfg::kStageBytes);
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
-      const uint16_t* kp = kt + (nb * 32 + li) * LD + 8 * hf;
+      const uint16_t* kp = kt + (sub + nb * 32 + li) * LD + 8 * hf;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 kop = *reinterpret_cast<const bf16x8*>(kp + ks * 16);
         s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[ks], s[nb], 0, 0, 0);
       }
     }
-    // ---- mask ---------------------------------------------------------------------------------
+  };
+
+  // ---- second half: mask, online softmax, O^T += V^T P^T ---------------------------------------
+  auto softmax_pv = [&](int t) __attribute__((always_inline)) {
+    const bool is_chunk = t >= n_ct;
+    const int base = share_base(t);
+    const uint16_t* vt =
+        reinterpret_cast<const uint16_t*>(smem + (size_t)(t & 1) * Cfg::kStageBytes + Cfg::kKTileBytes) + sub * LDV;
     const int limit = is_chunk ? (tok - base + 1) : (n_cache - base);   // keys kk < limit are visible
-    if (limit < kBN) {   // lane-varying for chunk tiles; only comparisons, no cross-lane traffic inside
+    if (limit < kSub) {   // lane-varying for chunk tiles; only comparisons, no cross-lane traffic inside
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -217,7 +215,6 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
           if (kk >= limit) s[nb][v] = -INFINITY;
         }
     }
-    // ---- online softmax -----------------------------------------------------------------------
     // The reference point m_run only moves when the tile maximum exceeds it by more than 2^kLazy:
     // exp2(s - m_run) then stays below 2^kLazy, and rescaling the accumulators becomes rare.
     float mx = -INFINITY;
@@ -239,23 +236,21 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
         for (int v = 0; v < 16; ++v) o[c][v] *= alpha;
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
-    __builtin_amdgcn_s_setprio(2);   // the wave feeding the matrix core goes first; its SIMD mate fills the gaps
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) s[nb][v] = __builtin_amdgcn_exp2f(fmaf(s[nb][v], sl2, -m_use));
-    // ---- O^T += V^T P^T -----------------------------------------------------------------------
     // lane's corner of every transposing read: key 4*hf + (lane%16)/4, dims 16*((lane/16)%2) + 4*(lane%4)
     const tr_ptr vtr = (tr_ptr)(vt + (4 * hf + ((lane & 15) >> 2)) * LDV + 16 * ((lane >> 4) & 1) + 4 * (lane & 3));
     float psum = 0.f;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        // k-slot e of this lane is key 16t + 8*(e/4) + 4*hf + e%4 of block nb
+      for (int t2 = 0; t2 < 2; ++t2) {
+        // k-slot e of this lane is key 16*t2 + 8*(e/4) + 4*hf + e%4 of block nb
         bf16x8 pb;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)s[nb][8 * t + e];
+        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)s[nb][8 * t2 + e];
         // row sum of the probabilities as the matrix core sees them (rounded to bf16)
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
@@ -264,7 +259,7 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
         }
 #pragma unroll
         for (int c = 0; c < DB; ++c) {
-          const int e0 = (nb * 32 + 16 * t) * LDV + c * 32;   // elements past the lane's corner
+          const int e0 = (nb * 32 + 16 * t2) * LDV + c * 32;   // elements past the lane's corner
           const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(vtr + e0 / 4);
           const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(vtr + (e0 + 8 * LDV) / 4);
           const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -273,11 +268,39 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
       }
     }
     l_run += psum;
-    __builtin_amdgcn_s_setprio(0);
-  }
+  };
 
-  // ---- merge of the two wave sets (NSETS == 2): set 1 hands (m, l, O) to set 0 through LDS ------------------------
-  if constexpr (NSETS == 2) {
+  // Both sets run the same program -- per tile: stage, barrier, issue, S = K Q^T, barrier, softmax and P V -- but set 1
+  // enters it one barrier late (and set 0 leaves it one barrier late), so the k-th barrier of set 0 is the (k-1)-th of
+  // set 1 and the sets stay half a step apart: while one forms S the other runs softmax and P V.
+  // Visibility: K of tile j is stored by set 0 before block barrier 2j and first read after it; V of tile j is stored
+  // by set 1 before block barrier 2j+1 (its own first barrier of the step) and first read, by set 0, after it.
+  // Reuse: a stage is overwritten two steps later, by the set that stored it, after that set's own last read; the
+  // other set's last read of it lies at least one block barrier earlier.
+  if (set == 1) __builtin_amdgcn_s_barrier();
+  for (int j = 0; j < n_tiles; ++j) {
+    {   // this set's tensor (K or V) of tile j: registers -> LDS
+      uint16_t* dst = reinterpret_cast<uint16_t*>(smem + (size_t)(j & 1) * Cfg::kStageBytes + stage_off_mine);
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) *reinterpret_cast<u32x4*>(dst + (r0 + RPI * i) * ld_mine + cg * 8) = R[i];
+    }
+    __syncthreads();
+    if (j + 1 < n_tiles) {
+      QUOKA_ISSUE(j + 1);
+      QUOKA_RESOLVE(j + 2);
+    }
+    if (!computes(j)) {   // nothing visible for this wave in its share of the tile
+      __builtin_amdgcn_s_barrier();
+      continue;
+    }
+    qk(j);
+    __builtin_amdgcn_s_barrier();
+    softmax_pv(j);
+  }
+  if (set == 0) __builtin_amdgcn_s_barrier();
+
+  // ---- merge of the two wave sets (SPLIT): set 1 hands (m, l, O) to set 0 through LDS ---------------------------
+  if constexpr (SPLIT) {
     constexpr int REC = 2 + DB * 16;
     float* mg = reinterpret_cast<float*>(smem) + (size_t)(slot * 64 + lane) * REC;   // both sets' waves of a slot share rows
     __syncthreads();   // all tiles consumed: the tile buffers may be reused
@@ -326,21 +349,21 @@ __global__ __launch_bounds__(64 * NW * NSETS, 2) void attn_bf16(Dims dm, AttnArg
 #undef QUOKA_RESOLVE
 #undef QUOKA_ISSUE
 
-template <int D, int NW, int NSETS>
-static hipError_t launch_dn(const Dims& dm, const AttnArgs& a, hipStream_t st) {
-  using Cfg = AttnCfg<D, NW>;
-  constexpr size_t lds = NSETS * Cfg::kLdsBytes;
+template <int D, bool SPLIT>
+static hipError_t launch_ds(const Dims& dm, const AttnArgs& a, hipStream_t st) {
+  using Cfg = AttnCfg<D, SPLIT>;
+  constexpr size_t lds = Cfg::kLdsBytes;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16<D, NW, NSETS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16<D, SPLIT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const int nrb = dm.g * ((dm.C + 31) / 32);
   const int half = (nrb + 1) / 2;
-  dim3 grid(dm.n_kv, (half + NW / 2 - 1) / (NW / 2), dm.b);
-  hipLaunchKernelGGL((attn_bf16<D, NW, NSETS>), grid, dim3(Cfg::kThreads * NSETS), lds, st, dm, a);
+  dim3 grid(dm.n_kv, (half + Cfg::HW - 1) / Cfg::HW, dm.b);
+  hipLaunchKernelGGL((attn_bf16<D, SPLIT>), grid, dim3(2 * kSetThreads), lds, st, dm, a);
   return hipGetLastError();
 }
 
@@ -348,10 +371,11 @@ template <int D>
 static hipError_t launch_d(const Dims& dm, const AttnArgs& a, hipStream_t st) {
   constexpr int kComputeUnits = 256;   // MI355X
   const int nrb = dm.g * ((dm.C + 31) / 32);
-  const long long blocks4 = (long long)dm.n_kv * (((nrb + 1) / 2 + 1) / 2) * dm.b;
-  // fewer than two 4-wave blocks per compute unit: use 8-wave blocks that split the KV tiles between two wave sets
-  if (blocks4 >= 2 * kComputeUnits) return launch_dn<D, 4, 1>(dm, a, st);
-  return launch_dn<D, 4, 2>(dm, a, st);
+  const long long blocks8 = (long long)dm.n_kv * (((nrb + 1) / 2 + 3) / 4) * dm.b;
+  // eight row blocks per block when that still gives every compute unit a block; otherwise four, with the keys of
+  // every tile split between the two wave sets
+  if (blocks8 >= kComputeUnits) return launch_ds<D, false>(dm, a, st);
+  return launch_ds<D, true>(dm, a, st);
 }
 
 hipError_t launch_attn_bf16(const Dims& dm, const AttnArgs& a, hipStream_t st) {
