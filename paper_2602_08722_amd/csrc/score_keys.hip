@@ -28,17 +28,22 @@ struct ScoreCfg {
   static constexpr int KG = 4 / QB;             // wave groups that split a tile's keys
   static constexpr int KPW = kScTile / KG;      // keys per wave per tile
   static constexpr size_t kTileBytes = (size_t)kScTile * LD * 2;
-  static constexpr size_t kLdsBytes = 2 * kTileBytes + 2 * kScTile * 4 + QB * kScTile * 4;
+  // two K tiles; three generations of squared norms and of per-query-block maxima (a tile's scores are finished
+  // one step after its products, under the next tile's barrier)
+  static constexpr size_t kLdsBytes = 2 * kTileBytes + 3 * kScTile * 4 + 3 * QB * kScTile * 4;
 };
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// sum of squares of the 8 bf16 values of a 16-byte chunk (products of bf16 pairs are exact in float32)
 __device__ __forceinline__ float sumsq_bf16x8(const u32x4& r) {
+  // (the chunk is reinterpreted as a whole: casting single dwords of the vector to bf16 pairs is miscompiled)
+  const bf16x8 v = __builtin_bit_cast(bf16x8, r);
   float s = 0.f;
-  const uint32_t w[4] = {r[0], r[1], r[2], r[3]};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const float a = __uint_as_float(w[i] << 16), b = __uint_as_float(w[i] & 0xFFFF0000u);
-    s += a * a;
-    s += b * b;
+    const bf16x2_t p = {v[2 * i], v[2 * i + 1]};
+    s = __builtin_amdgcn_fdot2_f32_bf16(p, p, s, false);
   }
   return s;
 }
@@ -53,8 +58,8 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* tile0p = reinterpret_cast<uint16_t*>(smem);
   uint16_t* tile1p = reinterpret_cast<uint16_t*>(smem + Cfg::kTileBytes);
-  float* ssq = reinterpret_cast<float*>(smem + 2 * Cfg::kTileBytes);   // [2][kScTile]
-  float* smax = ssq + 2 * kScTile;                                       // [QB][kScTile]
+  float* ssq = reinterpret_cast<float*>(smem + 2 * Cfg::kTileBytes);   // [3][kScTile]
+  float* smax = ssq + 3 * kScTile;                                       // [3][QB][kScTile]
 
   const int kv = blockIdx.y, b = blockIdx.z;
   const int T = min(kv_lens[b], dm.T_max);
@@ -62,26 +67,30 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
   if (t_begin >= T) return;  // block-uniform
   const int n_tiles = min(tiles_per_wg, (T - t_begin + kScTile - 1) / kScTile);
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qb = w % QB, kg = w / QB;
   const int li = lane & 31, hf = lane >> 5;
 
-  const uint16_t* kbase = kc + b * dm.kvs[0] + kv * dm.kvs[1];
+  // rows of this (batch, KV head) are addressed as base + 32-bit byte offset (the host checks the 4 GiB span)
+  const char* kbase = reinterpret_cast<const char*>(kc + b * dm.kvs[0] + kv * dm.kvs[1]);
+  const uint32_t row_bytes = (uint32_t)dm.kvs[2] * 2u;
   float* sc = scores + (size_t)(b * dm.n_kv + kv) * dm.T_max;
   const int cg = tid % CG, r0 = tid / CG;
 
-  u32x4 R[NLD];
-  auto issue = [&](int it) {
+  // two tiles are kept in flight: even tiles travel through RA, odd tiles through RB
+  u32x4 RA[NLD], RB[NLD];
+  auto issue = [&](int it, u32x4 (&R)[NLD]) __attribute__((always_inline)) {
     const int t0 = t_begin + it * kScTile;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       int row = t0 + r0 + RPI * i;
       row = row < T ? row : T - 1;  // tail rows re-read the last valid key; their scores are not stored
-      R[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)row * dm.kvs[2] + cg * 8);
+      R[i] = *reinterpret_cast<const u32x4*>(kbase + ((uint32_t)row * row_bytes + (uint32_t)cg * 16u));
     }
   };
-  issue(0);   // the first K tile is in flight while the query operands are prepared
-
+  issue(0, RA);   // the first K tiles are in flight while the query operands are prepared
+  if (n_tiles > 1) issue(1, RB);
 
   // Query operands: this wave's 32 query rows, split into three bf16 terms.
   bf16x8 a_hi[KS], a_mid[KS], a_lo[KS];
@@ -107,9 +116,25 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
     }
   }
 
-  for (int it = 0; it < n_tiles; ++it) {
-    const int buf = it & 1;
-    uint16_t* tl = buf ? tile1p : tile0p;
+  // scores of tile `it` from the maxima and squared norms of generation it % 3
+  auto finish = [&](int it) {
+    if (tid < kScTile) {
+      const int key = t_begin + it * kScTile + tid;
+      if (key < T) {
+        const float* sm = smax + (it % 3) * QB * kScTile;
+        float m = sm[tid];
+#pragma unroll
+        for (int j = 1; j < QB; ++j) m = fmaxf(m, sm[j * kScTile + tid]);
+        const float nrm = fmaxf(sqrtf(ssq[(it % 3) * kScTile + tid]), kNormEps);
+        sc[key] = m / nrm + 0.0f;
+      }
+    }
+  };
+
+  auto tile_step = [&](int it, u32x4 (&R)[NLD]) __attribute__((always_inline)) {
+    uint16_t* tl = (it & 1) ? tile1p : tile0p;
+    float* ssq_g = ssq + (it % 3) * kScTile;
+    float* smax_g = smax + (it % 3) * QB * kScTile;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int rl = r0 + RPI * i;
@@ -120,41 +145,57 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
       } else {
         ss = group_sum<CG>(ss);
       }
-      if (cg == 0) ssq[buf * kScTile + rl] = ss;
+      if (cg == 0) ssq_g[rl] = ss;
     }
+    // One barrier per tile.  It publishes tile `it` (and its squared norms) and the maxima of tile it-1.  The K tile
+    // buffer written above was last read two steps ago, before the previous barrier; the norm / maximum generation
+    // written in this step was last read (by finish) three steps ago, two barriers back.
     __syncthreads();
-    if (it + 1 < n_tiles) issue(it + 1);  // next tile's HBM loads fly during the MFMA loop
+    if (it + 2 < n_tiles) issue(it + 2, R);  // the registers are free again: fetch the tile after the next
+    if (it > 0) finish(it - 1);
 
+    // Products.  All three query terms go into one accumulator per key block (smallest term first inside every
+    // k-step), so there is nothing to add up afterwards; two key blocks are interleaved to keep the MFMA chains
+    // independent.
+    constexpr int NKB = KPW / 32;
 #pragma unroll
-    for (int kb = 0; kb < KPW / 32; ++kb) {
-      const int key_l = kg * KPW + kb * 32 + li;
-      const uint16_t* kp = tl + key_l * LD + 8 * hf;
-      f32x16 c_hi = {0}, c_mid = {0}, c_lo = {0};
+    for (int kb = 0; kb < NKB; kb += 2) {
+      constexpr int kPair = NKB >= 2 ? 2 : 1;
+      f32x16 c[kPair];
+      const uint16_t* kp[kPair];
+#pragma unroll
+      for (int u = 0; u < kPair; ++u) {
+        c[u] = f32x16{0};
+        kp[u] = tl + (kg * KPW + (kb + u) * 32 + li) * LD + 8 * hf;
+      }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 kop = *reinterpret_cast<const bf16x8*>(kp + ks * 16);
-        c_lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo[ks], kop, c_lo, 0, 0, 0);
-        c_mid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_mid[ks], kop, c_mid, 0, 0, 0);
-        c_hi = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[ks], kop, c_hi, 0, 0, 0);
+        bf16x8 kop[kPair];
+#pragma unroll
+        for (int u = 0; u < kPair; ++u) kop[u] = *reinterpret_cast<const bf16x8*>(kp[u] + ks * 16);
+#pragma unroll
+        for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo[ks], kop[u], c[u], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_mid[ks], kop[u], c[u], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[ks], kop[u], c[u], 0, 0, 0);
       }
-      float m = -INFINITY;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) m = fmaxf(m, c_hi[v] + (c_mid[v] + c_lo[v]));
-      m = fmaxf(m, other_half(m));
-      if (hf == 0) smax[qb * kScTile + key_l] = m;
-    }
-    __syncthreads();
-    if (tid < kScTile) {
-      const int key = t_begin + it * kScTile + tid;
-      if (key < T) {
-        float m = smax[tid];
+      for (int u = 0; u < kPair; ++u) {
+        float m = -INFINITY;
 #pragma unroll
-        for (int j = 1; j < QB; ++j) m = fmaxf(m, smax[j * kScTile + tid]);
-        const float nrm = fmaxf(sqrtf(ssq[buf * kScTile + tid]), kNormEps);
-        sc[key] = m / nrm + 0.0f;
+        for (int v = 0; v < 16; ++v) m = fmaxf(m, c[u][v]);
+        m = fmaxf(m, other_half(m));
+        if (hf == 0) smax_g[qb * kScTile + kg * KPW + (kb + u) * 32 + li] = m;
       }
     }
+  };
+  for (int it = 0; it < n_tiles; it += 2) {
+    tile_step(it, RA);
+    if (it + 1 < n_tiles) tile_step(it + 1, RB);
   }
+  __syncthreads();
+  finish(n_tiles - 1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -207,9 +248,11 @@ static hipError_t launch_bf16(const Dims& dm, const float* qbar, const void* kc,
   }
   const int nt = (dm.T_max + kScTile - 1) / kScTile;
   const int heads = dm.b * dm.n_kv;
-  const int wg_per_head = (1024 + heads - 1) / heads;
+  // two blocks per compute unit are resident at once: aim for one round of 512 blocks, so the query operands
+  // (prepared once per block) are amortised over as many tiles as the launch allows
+  const int wg_per_head = (512 + heads - 1) / heads;
   int tpw = (nt + wg_per_head - 1) / wg_per_head;
-  tpw = tpw < 1 ? 1 : (tpw > 8 ? 8 : tpw);
+  tpw = tpw < 1 ? 1 : tpw;
   dim3 grid((nt + tpw - 1) / tpw, dm.n_kv, dm.b);
   hipLaunchKernelGGL((score_bf16<D, QB>), grid, dim3(kScThreads), Cfg::kLdsBytes, st, dm, qbar,
                      static_cast<const uint16_t*>(kc), kv_lens, scores, n_keep, tpw);
