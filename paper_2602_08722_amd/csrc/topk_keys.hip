@@ -4,7 +4,7 @@
 // compaction so that indices come out in ascending position and equal scores go to the lower
 // position.  Integer work only: the result is deterministic and independent of the launch shape.
 //
-//   T_max <= kSmallMax : one 1024-thread block per head, keys held in LDS, one launch.
+//   T_max <= kSmallMax : one 1024-thread block per head, keys held in registers, one launch.
 //   larger             : several blocks per head.  Three histogram passes (11 + 11 + 10 bits, global
 //                        integer atomics) find the cut key; a count pass and an emit pass produce
 //                        the ordered index list.  Each pass re-derives the cut prefix from the
@@ -14,7 +14,7 @@
 
 namespace quoka {
 
-constexpr int kSmallMax = 16384;
+constexpr int kSmallMax = 32768;   // beyond this one compute unit's LDS atomics are slower than the multi-block path
 constexpr int kSmallThreads = 1024;
 constexpr int kLgThreads = 256;
 constexpr int kLgTile = 2048;          // scores per block in the multi-block path
@@ -24,18 +24,23 @@ __device__ __forceinline__ int radix_shift(int pass) { return pass == 0 ? 21 : (
 __device__ __forceinline__ uint32_t radix_bins(int pass) { return pass == 2 ? 1024u : 2048u; }
 
 // ---------------------------------------------------------------------------------------------
-// Single-block path.  Thread t keeps scores t*IPT .. t*IPT+IPT-1 in registers as order-preserving keys.
-// The radix select skips the leading bits that all keys share (scores of one head usually sit in a narrow
-// range, which would otherwise pile every key into one or two histogram bins of the first passes).
+// Single-block path.  Wave w owns scores [w*64*IPT, (w+1)*64*IPT); its register j of lane l is score
+// w*64*IPT + 64*j + l, so every load is a coalesced 256-byte row and position order inside a wave is (j, lane).
+// The radix select (8 bits per pass, LDS histogram) skips the leading bits that all keys share: scores of one head
+// usually sit in a narrow range, which would otherwise pile every key into one or two bins of the first passes.
+// The ordered compaction needs no scan over threads: per register, two wave ballots give every lane the number of
+// earlier taken positions of its wave, and the 16 wave totals are combined through LDS.
+
 template <int IPT>
 __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float* __restrict__ scores,
                                                            const int32_t* __restrict__ kv_lens,
                                                            const int32_t* __restrict__ budgets,
                                                            int32_t* __restrict__ k_idx, int32_t* __restrict__ k_cnt) {
+  constexpr int NW = kSmallThreads / 64;
   __shared__ uint32_t hist[256];
   __shared__ uint32_t s_prefix, s_need;
-  __shared__ uint32_t wsum[kSmallThreads / 64 + 1];
-  __shared__ uint32_t wmin[kSmallThreads / 64], wmax[kSmallThreads / 64];
+  __shared__ uint32_t wmin[NW], wmax[NW];
+  __shared__ uint32_t wgt[NW], weq[NW];
   const int kv = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int T = max(0, min(kv_lens[b], dm.T_max));
@@ -48,12 +53,12 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
     return;
   }
   const float* sc = scores + (size_t)(b * dm.n_kv + kv) * dm.T_max;
-  const int lo = tid * IPT;
+  const int lo = w * 64 * IPT + lane;   // position of register 0; register j is 64*j further
   uint32_t key[IPT];
   uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
-    const int t = lo + j;
+    const int t = lo + 64 * j;
     // padding key 0 sorts below the image of every real score, so it is never selected (B < T)
     key[j] = t < T ? okey(sc[t]) : 0u;
     if (t < T) {
@@ -74,7 +79,7 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
   kmin = wmin[0];
   kmax = wmax[0];
 #pragma unroll
-  for (int i = 1; i < kSmallThreads / 64; ++i) {
+  for (int i = 1; i < NW; ++i) {
     kmin = min(kmin, wmin[i]);
     kmax = max(kmax, wmax[i]);
   }
@@ -95,7 +100,7 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
 #pragma unroll
     for (int j = 0; j < IPT; ++j) {
       const uint32_t k = key[j];
-      if (lo + j < T && (k & mask) == prefix) atomicAdd(&hist[(k >> lo_bit) & dmask], 1u);
+      if (lo + 64 * j < T && (k & mask) == prefix) atomicAdd(&hist[(k >> lo_bit) & dmask], 1u);
     }
     __syncthreads();
     if (tid < 64) wave_find_bin256<true>(hist, s_need, lo_bit, &s_prefix, &s_need);   // descending: B largest
@@ -104,31 +109,38 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
     __syncthreads();
   }
   const uint32_t tau = s_prefix, need_eq = s_need;
+  // wave totals of (key > tau) and (key == tau)
   uint32_t c_gt = 0, c_eq = 0;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
-    const bool in = lo + j < T;
-    c_gt += in && (key[j] > tau);
-    c_eq += in && (key[j] == tau);
+    const bool in = lo + 64 * j < T;
+    c_gt += __popcll(__builtin_amdgcn_ballot_w64(in && key[j] > tau));
+    c_eq += __popcll(__builtin_amdgcn_ballot_w64(in && key[j] == tau));
   }
-  uint32_t tot;
-  uint32_t p_gt = block_excl_scan<kSmallThreads>(c_gt, wsum, &tot);
-  uint32_t p_eq = block_excl_scan<kSmallThreads>(c_eq, wsum, &tot);
-  uint32_t pos = p_gt + min(p_eq, need_eq);
+  if (lane == 0) {
+    wgt[w] = c_gt;
+    weq[w] = c_eq;
+  }
+  __syncthreads();
+  uint32_t n_gt = 0, n_eq = 0;   // taken candidates at earlier positions: greater than the cut / equal to it
+  for (int i = 0; i < w; ++i) {
+    n_gt += wgt[i];
+    n_eq += weq[i];
+  }
+  const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
-    if (lo + j < T) {
-      const uint32_t k = key[j];
-      bool take = k > tau;
-      if (k == tau) {
-        take = p_eq < need_eq;
-        ++p_eq;
-      }
-      if (take) {
-        if (pos < (uint32_t)B) out[pos] = lo + j;   // guard: a malformed score array cannot push writes past the budget
-        ++pos;
-      }
+    const int t = lo + 64 * j;
+    const bool in = t < T;
+    const bool gt = in && key[j] > tau, eq = in && key[j] == tau;
+    const unsigned long long m_gt = __builtin_amdgcn_ballot_w64(gt), m_eq = __builtin_amdgcn_ballot_w64(eq);
+    const uint32_t gt_before = n_gt + __popcll(m_gt & below), eq_before = n_eq + __popcll(m_eq & below);
+    if (gt || (eq && eq_before < need_eq)) {   // equal scores go to the lower positions
+      const uint32_t pos = gt_before + min(eq_before, need_eq);
+      if (pos < (uint32_t)B) out[pos] = t;     // guard: a malformed score array cannot push writes past the budget
     }
+    n_gt += __popcll(m_gt);
+    n_eq += __popcll(m_eq);
   }
 }
 
@@ -334,8 +346,10 @@ hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* 
       hipLaunchKernelGGL((topk_small<4>), grid, block, 0, st, dm, scores, kv_lens, budgets, k_idx, k_cnt);
     } else if (ipt <= 8) {
       hipLaunchKernelGGL((topk_small<8>), grid, block, 0, st, dm, scores, kv_lens, budgets, k_idx, k_cnt);
-    } else {
+    } else if (ipt <= 16) {
       hipLaunchKernelGGL((topk_small<16>), grid, block, 0, st, dm, scores, kv_lens, budgets, k_idx, k_cnt);
+    } else {
+      hipLaunchKernelGGL((topk_small<32>), grid, block, 0, st, dm, scores, kv_lens, budgets, k_idx, k_cnt);
     }
     return hipGetLastError();
   }

@@ -138,8 +138,12 @@ TOPK_CASES = [
     ([20000, 33000, 0, 17000], [2000, 33000, 5, 1], 33000, "normal"),
     ([131072], [8192], 131072, "normal"),
     ([131072], [8192], 131072, "const"),
-    ([16384], [16383], 16384, "normal"),                    # largest single-block size, budget T-1
-    ([16385], [1], 16385, "signed"),                        # smallest multi-block size
+    ([16384], [16383], 16384, "normal"),                    # budget T-1
+    ([16385], [1], 16385, "signed"),
+    ([32768], [7000], 32768, "normal"),                     # largest single-block size
+    ([32768, 20000], [33, 19999], 32768, "ties"),
+    ([32769], [100], 32769, "ties"),                        # smallest multi-block size
+    ([65000, 40000], [33, 39999], 65536, "ties"),
     ([1], [1], 1, "normal"),
     ([3, 1, 2], [2, 5, 1], 3, "ties"),
 ]
