@@ -111,44 +111,78 @@ __global__ __launch_bounds__(kSqThreads) void sq_cosine(Dims dm, const T* __rest
 
 // ---------------------------------------------------------------------------------------------
 // One block per (b, q-head): the N' lowest cosines in rank order.  Thread t keeps cosines t*IPT .. t*IPT+IPT-1
-// in registers as order-preserving keys; LDS radix select (8 bits per pass, ties to the lower position),
-// then the rank of every retained query among the retained ones by counting, spread over the whole block.
+// in registers as order-preserving keys; LDS radix select (8 bits per pass, ties to the lower position) that
+// starts below the leading bits all keys share (cosines to the mean sit in a narrow range), then the rank of
+// every retained query among the retained ones by counting, spread over the whole block.
 constexpr int kMaxKeep = 128;
+constexpr int kSelThreads = 1024;
 
 template <int IPT>
-__global__ __launch_bounds__(kSqThreads) void sq_select(Dims dm, const float* __restrict__ cosv,
-                                                       int32_t* __restrict__ q_idx, int n_keep) {
+__global__ __launch_bounds__(kSelThreads) void sq_select(Dims dm, const float* __restrict__ cosv,
+                                                        int32_t* __restrict__ q_idx, int n_keep) {
+  constexpr int NW = kSelThreads / 64;
   __shared__ uint32_t hist[256];
   __shared__ uint32_t s_prefix, s_need, n_sel;
-  __shared__ uint32_t wsum[kSqThreads / 64 + 1];
+  __shared__ uint32_t wsum[NW + 1];
+  __shared__ uint32_t wmin[NW], wmax[NW];
   __shared__ uint32_t sel_key[kMaxKeep];
   __shared__ uint32_t sel_idx[kMaxKeep];
   const int h = blockIdx.x, b = blockIdx.y;
   const int C = dm.C;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const float* cv = cosv + (size_t)(b * dm.n_q + h) * C;
   const int lo = tid * IPT;
   uint32_t key[IPT];
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
 #pragma unroll
-  for (int j = 0; j < IPT; ++j) key[j] = lo + j < C ? okey(cv[lo + j]) : 0xFFFFFFFFu;
+  for (int j = 0; j < IPT; ++j) {
+    key[j] = lo + j < C ? okey(cv[lo + j]) : 0xFFFFFFFFu;
+    if (lo + j < C) {
+      kmin = min(kmin, key[j]);
+      kmax = max(kmax, key[j]);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+  }
+  if (lane == 0) {
+    wmin[w] = kmin;
+    wmax[w] = kmax;
+  }
+  __syncthreads();
+  kmin = wmin[0];
+  kmax = wmax[0];
+#pragma unroll
+  for (int i = 1; i < NW; ++i) {
+    kmin = min(kmin, wmin[i]);
+    kmax = max(kmax, wmax[i]);
+  }
+  const uint32_t diff = kmin ^ kmax;
+  int hi = diff ? 32 - __clz(diff) : 0;                                    // keys agree on all bits >= hi
+  uint32_t mask = hi >= 32 ? 0u : ~((hi == 0) ? 0u : ((1u << hi) - 1u));   // decided bits
   if (tid == 0) {
-    s_prefix = 0;
+    s_prefix = kmin & mask;
     s_need = (uint32_t)n_keep;   // rank (1-based, ascending) of the cut element
     n_sel = 0;
   }
-  uint32_t mask = 0;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    hist[tid] = 0;   // kSqThreads == 256 bins
+  __syncthreads();
+  while (hi > 0) {
+    const int lo_bit = max(hi - 8, 0);
+    const uint32_t dmask = (1u << (hi - lo_bit)) - 1u;
+    if (tid < 256) hist[tid] = 0;
     __syncthreads();
     const uint32_t prefix = s_prefix;
 #pragma unroll
     for (int j = 0; j < IPT; ++j) {
       const uint32_t k = key[j];
-      if (lo + j < C && (k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+      if (lo + j < C && (k & mask) == prefix) atomicAdd(&hist[(k >> lo_bit) & dmask], 1u);
     }
     __syncthreads();
-    if (tid < 64) wave_find_bin256<false>(hist, s_need, shift, &s_prefix, &s_need);   // ascending: smallest
-    mask |= 255u << shift;
+    if (tid < 64) wave_find_bin256<false>(hist, s_need, lo_bit, &s_prefix, &s_need);   // ascending: smallest
+    mask |= dmask << lo_bit;
+    hi = lo_bit;
     __syncthreads();
   }
   const uint32_t tau = s_prefix;      // key of the n_keep-th smallest cosine
@@ -157,7 +191,7 @@ __global__ __launch_bounds__(kSqThreads) void sq_select(Dims dm, const float* __
 #pragma unroll
   for (int j = 0; j < IPT; ++j) c_eq += (lo + j < C) && (key[j] == tau);
   uint32_t tot_eq;
-  uint32_t eq_rank = block_excl_scan<kSqThreads>(c_eq, wsum, &tot_eq);
+  uint32_t eq_rank = block_excl_scan<kSelThreads>(c_eq, wsum, &tot_eq);
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
     if (lo + j < C) {
@@ -180,7 +214,7 @@ __global__ __launch_bounds__(kSqThreads) void sq_select(Dims dm, const float* __
   // rank by counting: P consecutive lanes share one retained query and split the comparisons
   int nk2 = 1;
   while (nk2 < n_keep) nk2 <<= 1;
-  const int P = kSqThreads / nk2;          // 2 .. 256, a power of two
+  const int P = kSelThreads / nk2;         // 8 .. 1024, a power of two
   const int e = tid / P, part = tid % P;
   int rank = 0;
   if (e < n_keep) {
@@ -191,9 +225,9 @@ __global__ __launch_bounds__(kSqThreads) void sq_select(Dims dm, const float* __
     }
   }
   for (int o = 1; o < P && o < 64; o <<= 1) rank += __shfl_xor(rank, o, kWave);
-  if (P > 64) {   // n_keep < 4: the lanes of one query span waves; let lane 0 of each wave add through LDS
+  if (P > 64) {   // n_keep < 16: the lanes of one query span waves; let lane 0 of each wave add through LDS
     __syncthreads();
-    if ((tid & 63) == 0) wsum[tid >> 6] = (uint32_t)rank;
+    if (lane == 0) wsum[w] = (uint32_t)rank;
     __syncthreads();
     rank = 0;
     const int w0 = (e * P) >> 6;
@@ -264,16 +298,16 @@ static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, fl
     dim3 grid(n_tiles, dm.n_q, dm.b);
     hipLaunchKernelGGL((sq_partial_sums<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, n_tiles);
     hipLaunchKernelGGL((sq_cosine<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, ws_cos, n_tiles);
-    const dim3 sgrid(dm.n_q, dm.b), sblock(kSqThreads);
-    const int ipt = (dm.C + kSqThreads - 1) / kSqThreads;
-    if (ipt <= 4) {
+    const dim3 sgrid(dm.n_q, dm.b), sblock(kSelThreads);
+    const int ipt = (dm.C + kSelThreads - 1) / kSelThreads;
+    if (ipt <= 1) {
+      hipLaunchKernelGGL((sq_select<1>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+    } else if (ipt <= 2) {
+      hipLaunchKernelGGL((sq_select<2>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+    } else if (ipt <= 4) {
       hipLaunchKernelGGL((sq_select<4>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
-    } else if (ipt <= 8) {
-      hipLaunchKernelGGL((sq_select<8>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
-    } else if (ipt <= 16) {
-      hipLaunchKernelGGL((sq_select<16>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
     } else {
-      hipLaunchKernelGGL((sq_select<32>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+      hipLaunchKernelGGL((sq_select<8>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
     }
   } else {
     hipLaunchKernelGGL(sq_identity, dim3(dm.n_q, dm.b), dim3(64), 0, st, dm, q_idx, n_keep);
