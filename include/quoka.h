@@ -136,6 +136,26 @@ quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const voi
                               int32_t* k_cnt, void* out, float* lse, void* workspace, size_t workspace_bytes,
                               void* stream);
 
+/* Chunked prefill of a whole prompt, one layer (Alg. 2: for every chunk select, attend, then append the chunk to
+ * the cache).  K and V hold the whole prompt, so the chunk's keys and values already sit behind the cache rows and
+ * the append step is the cache length moving forward by one chunk: nothing is copied.
+ *   shape     chunk_len = B_CP; max_kv_len = L, the prompt length (extent of the token axis of q, k, v and out);
+ *             kv_stride describes K and V [b, n_KV, L, d]; ck_stride is ignored (chunk rows are rows of K and V);
+ *             q_stride / o_stride describe Q and O [b, n_Q, L, d].  All sequences of the batch have length L.
+ *   q, k, v   in  (shape.dtype);  out  [b, n_Q, L, d] (shape.dtype)
+ *   kv_lens_all  in  [n_chunks, b] int32, n_chunks = ceil(L / chunk_len): the cache length before chunk i, i.e.
+ *                i * chunk_len in every entry (a device array because every stage reads its lengths from memory)
+ *   budgets_all  in  [n_chunks, b] int32: B_SA for chunk i (ignored when sparse == 0)
+ *   sparse    non-zero: quoka_chunk_attn per chunk; zero: quoka_dense_attn per chunk (the baseline of Eq. 2, which
+ *             over a whole prompt equals plain causal attention)
+ *   q_idx, qbar, scores, k_idx, k_cnt   scratch for one chunk, shaped as in quoka_chunk_attn; they hold the last
+ *             chunk's intermediates on return (unused when sparse == 0, may then be NULL)
+ * The last chunk may be shorter than chunk_len.  Everything is enqueued on `stream`, chunk after chunk.          */
+quoka_status quoka_prefill_attn(const quoka_shape* shape, int sparse, const void* q, const void* k, const void* v,
+                                const int32_t* kv_lens_all, const int32_t* budgets_all, int32_t* q_idx, float* qbar,
+                                float* scores, int32_t* k_idx, int32_t* k_cnt, void* out, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
 const char* quoka_status_string(quoka_status status);
 
 /* major * 10000 + minor * 100 + patch */

@@ -21,7 +21,8 @@ _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = (
     "quoka_workspace_bytes", "quoka_select_queries", "quoka_score_keys", "quoka_topk_keys",
-    "quoka_sparse_attn", "quoka_dense_attn", "quoka_chunk_attn", "quoka_status_string", "quoka_version",
+    "quoka_sparse_attn", "quoka_dense_attn", "quoka_chunk_attn", "quoka_prefill_attn", "quoka_status_string",
+    "quoka_version",
 )
 
 
@@ -68,7 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.quoka_sparse_attn.argtypes = [SH, P, P, P, I32P, I32P, P, P, P, F32P, P, SZ, P]
     lib.quoka_dense_attn.argtypes = [SH, P, P, P, I32P, P, P, P, F32P, P, SZ, P]
     lib.quoka_chunk_attn.argtypes = [SH, P, P, P, I32P, I32P, P, P, I32P, F32P, F32P, I32P, I32P, P, F32P, P, SZ, P]
-    for name in EXPORTS[:7]:
+    lib.quoka_prefill_attn.argtypes = [SH, ctypes.c_int, P, P, P, I32P, I32P, I32P, F32P, F32P, I32P, I32P, P, P, SZ, P]
+    for name in EXPORTS[:8]:
         getattr(lib, name).restype = ctypes.c_int
     lib.quoka_status_string.argtypes = [ctypes.c_int]
     lib.quoka_status_string.restype = ctypes.c_char_p
@@ -168,6 +170,48 @@ def quoka_chunk_attn(shape, q, k_cache, v_cache, kv_lens, budgets, k_chunk, v_ch
         ctypes.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_lens), _ptr(budgets), _ptr(k_chunk),
         _ptr(v_chunk), _ptr(q_idx), _ptr(qbar), _ptr(scores), _ptr(k_idx), _ptr(k_cnt), _ptr(out), _ptr(lse),
         _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def quoka_prefill_attn(shape, sparse, q, k, v, kv_lens_all, budgets_all, q_idx, qbar, scores, k_idx, k_cnt, out,
+                       workspace, stream=None) -> None:
+    _check("quoka_prefill_attn", load_library().quoka_prefill_attn(
+        ctypes.byref(shape), int(bool(sparse)), _ptr(q), _ptr(k), _ptr(v), _ptr(kv_lens_all), _ptr(budgets_all),
+        _ptr(q_idx), _ptr(qbar), _ptr(scores), _ptr(k_idx), _ptr(k_cnt), _ptr(out), _ptr(workspace),
+        workspace.numel(), _stream(stream)))
+
+
+class PrefillBuffers:
+    """Device buffers for chunked prefill of a whole prompt (allocation only; torch owns the memory).
+
+    q [b, n_Q, L, d], k / v [b, n_KV, L, d]; `budget` is B_SA per chunk: an int, or a callable of the cache length.
+    """
+
+    def __init__(self, q, k, v, chunk, n_retain, budget):
+        dev = q.device
+        b, n_q, L, d = q.shape
+        n_kv = k.shape[1]
+        self.q, self.k, self.v = q, k, v
+        n_chunks = -(-L // chunk)
+        lens = [[i * chunk] * b for i in range(n_chunks)]
+        bud = [[int(budget(i * chunk)) if callable(budget) else int(budget)] * b for i in range(n_chunks)]
+        max_budget = max(0, min(max(x[0] for x in bud), L))
+        self.kv_lens_all = torch.tensor(lens, dtype=torch.int32, device=dev)
+        self.budgets_all = torch.tensor(bud, dtype=torch.int32, device=dev)
+        self.out = torch.empty_like(q)
+        # the shape describes one chunk of `chunk` rows taken from the prompt tensors (their strides, no copies)
+        self.shape = make_shape(q[:, :, :chunk], k, k[:, :, :chunk], self.out[:, :, :chunk], n_retain, max_budget)
+        n_keep = self.shape.n_keep
+        self.q_idx = torch.empty((b, n_q, n_keep), dtype=torch.int32, device=dev)
+        self.qbar = torch.empty((b, n_kv, n_keep, d), dtype=torch.float32, device=dev)
+        self.scores = torch.empty((b, n_kv, L), dtype=torch.float32, device=dev)
+        self.k_idx = torch.empty((b, n_kv, max(max_budget, 1)), dtype=torch.int32, device=dev)
+        self.k_cnt = torch.empty((b, n_kv), dtype=torch.int32, device=dev)
+        self.workspace = torch.empty(quoka_workspace_bytes(self.shape), dtype=torch.uint8, device=dev)
+
+    def run(self, sparse=True):
+        quoka_prefill_attn(self.shape, sparse, self.q, self.k, self.v, self.kv_lens_all, self.budgets_all, self.q_idx,
+                           self.qbar, self.scores, self.k_idx, self.k_cnt, self.out, self.workspace)
+        return self.out
 
 
 class ChunkBuffers:

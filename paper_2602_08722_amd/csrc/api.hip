@@ -208,6 +208,40 @@ quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const voi
                            workspace_bytes, stream);
 }
 
+quoka_status quoka_prefill_attn(const quoka_shape* shape, int sparse, const void* q, const void* k, const void* v,
+                                const int32_t* kv_lens_all, const int32_t* budgets_all, int32_t* q_idx, float* qbar,
+                                float* scores, int32_t* k_idx, int32_t* k_cnt, void* out, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+  Dims dm;
+  quoka_status st = check_shape(shape, &dm);
+  if (st != QUOKA_OK) return st;
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || kv_lens_all == nullptr) return QUOKA_EINVAL;
+  if (sparse && budgets_all == nullptr) return QUOKA_EINVAL;
+  const int L = shape->max_kv_len, C = shape->chunk_len;
+  if (L < 1) return QUOKA_EINVAL;
+  const size_t es = shape->dtype == QUOKA_BF16 ? 2 : 4;
+  const int n_chunks = (L + C - 1) / C;
+  for (int i = 0; i < n_chunks; ++i) {
+    quoka_shape sh = *shape;
+    sh.chunk_len = (i + 1) * C <= L ? C : L - i * C;   // the last chunk may be short
+    for (int a = 0; a < 3; ++a) sh.ck_stride[a] = shape->kv_stride[a];
+    const size_t tok = (size_t)i * C;
+    const char* qi = static_cast<const char*>(q) + tok * shape->q_stride[2] * es;
+    const char* ki = static_cast<const char*>(k) + tok * shape->kv_stride[2] * es;
+    const char* vi = static_cast<const char*>(v) + tok * shape->kv_stride[2] * es;
+    char* oi = static_cast<char*>(out) + tok * shape->o_stride[2] * es;
+    const int32_t* lens = kv_lens_all + (size_t)i * shape->batch;
+    if (sparse) {
+      st = quoka_chunk_attn(&sh, qi, k, v, lens, budgets_all + (size_t)i * shape->batch, ki, vi, q_idx, qbar, scores,
+                            k_idx, k_cnt, oi, nullptr, workspace, workspace_bytes, stream);
+    } else {
+      st = quoka_dense_attn(&sh, qi, k, v, lens, ki, vi, oi, nullptr, workspace, workspace_bytes, stream);
+    }
+    if (st != QUOKA_OK) return st;
+  }
+  return QUOKA_OK;
+}
+
 const char* quoka_status_string(quoka_status status) {
   switch (status) {
     case QUOKA_OK: return "ok";

@@ -113,6 +113,10 @@ def test_bad_strides_and_null_pointers_are_rejected_without_a_launch(pk):
                                 None) == 1
     assert lib.quoka_chunk_attn(ctypes.byref(s), None, fake, fake, fake, fake, fake, fake, fake, fake, fake, fake,
                                 fake, fake, None, ws_ok, big, None) == 1
+    assert lib.quoka_prefill_attn(ctypes.byref(s), 1, fake, None, fake, fake, fake, fake, fake, fake, fake, fake, fake,
+                                  ws_ok, big, None) == 1
+    assert lib.quoka_prefill_attn(ctypes.byref(s), 1, fake, fake, fake, fake, None, fake, fake, fake, fake, fake, fake,
+                                  ws_ok, big, None) == 1   # sparse prefill needs budgets
     assert lib.quoka_workspace_bytes(None, ctypes.byref(ctypes.c_size_t(0))) == 1
 
 
