@@ -42,6 +42,10 @@ def _parse():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate-mib", type=int, default=640, help="total MiB of distinct K/V copies to rotate over")
+    ap.add_argument("--prefill-sweep", default=None, metavar="L1,L2,...",
+                    help="instead of the chunk benchmark: whole-prompt chunked prefill (quoka_prefill_attn, one layer "
+                         "of the c2 shape, chunk 1024, N_Q 64, budget 12 %% of the cache) at these prompt lengths, "
+                         "sparse against dense; prints one JSON object")
     ap.add_argument("--profile-stage", default=None,
                     choices=["select_queries", "score_keys", "topk_keys", "sparse_attn", "dense_attn", "copy"],
                     help="run only this stage --steps times (for rocprofv3 counter passes) and print a short JSON; "
@@ -93,6 +97,34 @@ def _cpu_baseline(w):
                        + ("; scaled by the batch size" if w.batch > 1 else ""))}
 
 
+def _prefill_sweep(args, torch, pk, dev):
+    """Whole-prompt attention time of one layer against the prompt length (the shape of the paper's
+    speedup-versus-length plots, on synthetic activations)."""
+    n_q, n_kv, d, chunk, n_retain = 32, 8, 128, 1024, 64
+    rows = []
+    for L in [int(x) for x in args.prefill_sweep.split(",")]:
+        g = torch.Generator(device=dev).manual_seed(L)
+        q = torch.randn(1, n_q, L, d, device=dev, generator=g).bfloat16()
+        k = torch.randn(1, n_kv, L, d, device=dev, generator=g).bfloat16()
+        v = torch.randn(1, n_kv, L, d, device=dev, generator=g).bfloat16()
+        pb = pk.PrefillBuffers(q, k, v, chunk, n_retain, budget=lambda t: int(0.12 * t))
+        res = {}
+        for name, sparse in (("sparse", True), ("dense", False)):
+            pb.run(sparse=sparse)
+            torch.cuda.synchronize()
+            reps = max(1, min(10, (1 << 17) // L))
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                pb.run(sparse=sparse)
+            torch.cuda.synchronize()
+            res[name] = (time.perf_counter() - t0) * 1e3 / reps
+        rows.append({"prompt_len": L, "sparse_ms": res["sparse"], "dense_ms": res["dense"],
+                     "speedup": res["dense"] / res["sparse"]})
+        del pb, q, k, v
+    print(json.dumps({"mode": "prefill_sweep", "layer": f"n_q={n_q} n_kv={n_kv} d={d} chunk={chunk} N_Q={n_retain} "
+                      "budget=12% of the cache", "data": "synthetic", "rows": rows}))
+
+
 def main():
     args = _parse()
     if args.gpus != 1:
@@ -107,6 +139,9 @@ def main():
     pk.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
+    if args.prefill_sweep:
+        _prefill_sweep(args, torch, pk, dev)
+        return
     w = gen.make_workload(args.workload)
     t = gen.to_torch(w, dev)
     es = 2 if w.dtype == "bf16" else 4
