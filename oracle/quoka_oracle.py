@@ -78,55 +78,78 @@ def unit(x: np.ndarray) -> np.ndarray:
     return x / np.maximum(n, EPS)
 
 
-def group_mean_queries(Q: np.ndarray, q_idx: np.ndarray, n_kv: int) -> np.ndarray:
+def group_mean_queries(Q: np.ndarray, q_idx: np.ndarray, n_kv: int, similarity: str = "cosine") -> np.ndarray:
     """Q-bar [n_kv, N', d]: mean over each KV group of the unit retained queries.
 
     Alg. 1, pre-aggregation step: reshape (n_kv, n_q/n_kv, N_Q, d) and average
     the group axis; the r-th retained query of every head in a group is paired.
+    similarity="dot" is the ablation of Sec. 3.2 (dot products instead of
+    cosines): the retained queries are averaged without normalisation.
     """
+    assert similarity in ("cosine", "dot")
     Q = np.asarray(Q, dtype=np.float64)
     n_q = Q.shape[0]
     g = n_q // n_kv
     Qr = np.stack([Q[h, q_idx[h]] for h in range(n_q)])  # [n_q, N', d]
-    Qr = unit(Qr)
+    if similarity == "cosine":
+        Qr = unit(Qr)
     return Qr.reshape(n_kv, g, Qr.shape[1], Qr.shape[2]).mean(axis=1)
 
 
 # ---------------------------------------------------------------------------
 # Alg. 1, scoring and aggregation
 # ---------------------------------------------------------------------------
-def key_scores(Q: np.ndarray, q_idx: np.ndarray, K: np.ndarray, n_kv: int) -> np.ndarray:
+def key_scores(Q: np.ndarray, q_idx: np.ndarray, K: np.ndarray, n_kv: int, similarity: str = "cosine",
+               reduce: str = "max") -> np.ndarray:
     """S-hat [n_kv, T], literal (post-hoc) form of Sec. 3.2-3.3.
 
     Per q-head cosine between every retained query and every key, averaged over
     the heads of a KV group, then the maximum over the retained-query axis.
+    The two ablations of Sec. 3.2-3.3 (appendix tables on scoring and aggregation):
+    similarity="dot" scores with plain dot products (no normalisation of queries
+    or keys); reduce="mean" averages over the retained-query axis instead of
+    taking the maximum.
     """
+    assert similarity in ("cosine", "dot") and reduce in ("max", "mean")
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     n_q = Q.shape[0]
     g = n_q // n_kv
     T = K.shape[1]
-    Kn = unit(K)
+    Kn = unit(K) if similarity == "cosine" else K
     out = np.empty((n_kv, T), dtype=np.float64)
     for kv in range(n_kv):
         acc = None
         for j in range(g):
             h = kv * g + j
-            qn = unit(Q[h, q_idx[h]])            # [N', d]
-            S = qn @ Kn[kv].T                    # cosines [N', T]
+            qn = Q[h, q_idx[h]]                  # [N', d]
+            if similarity == "cosine":
+                qn = unit(qn)
+            S = qn @ Kn[kv].T                    # cosines (or dot products) [N', T]
             acc = S if acc is None else acc + S
-        out[kv] = (acc / g).max(axis=0) if T > 0 else np.empty((0,))
+        if T == 0:
+            out[kv] = np.empty((0,))
+        else:
+            out[kv] = (acc / g).max(axis=0) if reduce == "max" else (acc / g).mean(axis=0)
     return out
 
 
-def key_scores_preagg(qbar: np.ndarray, K: np.ndarray) -> np.ndarray:
-    """S-hat [n_kv, T] from a given Q-bar: max_r <Q-bar_r, K_t / ||K_t||> (Alg. 1, S and S-hat steps)."""
+def key_scores_preagg(qbar: np.ndarray, K: np.ndarray, similarity: str = "cosine", reduce: str = "max") -> np.ndarray:
+    """S-hat [n_kv, T] from a given Q-bar: max_r <Q-bar_r, K_t / ||K_t||> (Alg. 1, S and S-hat steps);
+    the ablation variants as in key_scores."""
+    assert similarity in ("cosine", "dot") and reduce in ("max", "mean")
     qbar = np.asarray(qbar, dtype=np.float64)
-    Kn = unit(np.asarray(K, dtype=np.float64))
+    Kn = np.asarray(K, dtype=np.float64)
+    if similarity == "cosine":
+        Kn = unit(Kn)
     n_kv, T = Kn.shape[0], Kn.shape[1]
     out = np.empty((n_kv, T), dtype=np.float64)
     for kv in range(n_kv):
-        out[kv] = (qbar[kv] @ Kn[kv].T).max(axis=0) if T > 0 else np.empty((0,))
+        if T == 0:
+            out[kv] = np.empty((0,))
+        else:
+            S = qbar[kv] @ Kn[kv].T
+            out[kv] = S.max(axis=0) if reduce == "max" else S.mean(axis=0)
     return out
 
 
@@ -208,11 +231,12 @@ def dense_attn(Q, K, V, Kc, Vc, return_lse: bool = False, rows=None, heads=None)
     return sparse_attn(Q, K, V, full, Kc, Vc, return_lse, rows, heads)
 
 
-def quoka_select(Q, K, n_retain: int, budget: int):
-    """Alg. 1 up to the index set: returns (q_idx, scores, k_idx)."""
+def quoka_select(Q, K, n_retain: int, budget: int, similarity: str = "cosine", reduce: str = "max"):
+    """Alg. 1 up to the index set: returns (q_idx, scores, k_idx).  The query sub-selection is the same for the
+    ablation scorers; only the key scores change."""
     n_kv = np.asarray(K).shape[0]
     q_idx = select_queries(Q, n_retain)
-    scores = key_scores(Q, q_idx, K, n_kv)
+    scores = key_scores(Q, q_idx, K, n_kv, similarity, reduce)
     k_idx = topk_keys(scores, budget)
     return q_idx, scores, k_idx
 

@@ -125,3 +125,55 @@ def test_planted_heavy_keys_of_config1_are_selected():
     heavy = scores[0, w.notes["heavy_key_pos"]]
     assert np.all(heavy > 0.35)
     assert np.quantile(scores[0], 0.99) < 0.35
+
+
+# ---- ablation scorers (Sec. 3.2: dot product instead of cosine; Sec. 3.3: mean instead of max over queries) ----
+def _brute_scores(Q, q_idx, K, n_kv, normalise, reduce):
+    """Element-by-element Python loops over the definition."""
+    n_q, g, T = Q.shape[0], Q.shape[0] // n_kv, K.shape[1]
+    out = np.zeros((n_kv, T))
+    for kv in range(n_kv):
+        for t in range(T):
+            k = K[kv, t].astype(np.float64)
+            if normalise:
+                k = k / max(np.linalg.norm(k), 1e-8)
+            per_query = []
+            for r in range(q_idx.shape[1]):
+                acc = 0.0
+                for j in range(g):
+                    q = Q[kv * g + j, q_idx[kv * g + j, r]].astype(np.float64)
+                    if normalise:
+                        q = q / max(np.linalg.norm(q), 1e-8)
+                    acc += float(np.dot(q, k))
+                per_query.append(acc / g)
+            out[kv, t] = max(per_query) if reduce == "max" else sum(per_query) / len(per_query)
+    return out
+
+
+@pytest.mark.parametrize("similarity,reduce", [("dot", "max"), ("cosine", "mean"), ("dot", "mean")])
+def test_ablation_scorers_match_brute_force_and_preaggregation(similarity, reduce):
+    rng = np.random.default_rng(77)
+    n_q, n_kv, C, T, d = 4, 2, 12, 9, 8
+    Q = rng.normal(size=(n_q, C, d)) * rng.uniform(0.2, 5.0, size=(n_q, C, 1))   # norms vary: dot != cosine
+    K = rng.normal(size=(n_kv, T, d)) * rng.uniform(0.2, 5.0, size=(n_kv, T, 1))
+    q_idx = O.select_queries(Q, 5)
+    want = _brute_scores(Q, q_idx, K, n_kv, similarity == "cosine", reduce)
+    got = O.key_scores(Q, q_idx, K, n_kv, similarity, reduce)
+    assert np.allclose(got, want, rtol=0, atol=1e-12)
+    qbar = O.group_mean_queries(Q, q_idx, n_kv, similarity)
+    assert np.allclose(O.key_scores_preagg(qbar, K, similarity, reduce), want, rtol=0, atol=1e-12)
+    # the variants really differ from the method's scorer on these inputs
+    assert np.abs(got - O.key_scores(Q, q_idx, K, n_kv)).max() > 1e-3
+
+
+def test_ablation_scorers_degenerate_cases():
+    rng = np.random.default_rng(78)
+    Q = O.unit(rng.normal(size=(2, 6, 8)))
+    K = O.unit(rng.normal(size=(1, 7, 8)))
+    q_idx = O.select_queries(Q, 6)
+    # unit-norm inputs: dot product and cosine coincide
+    assert np.allclose(O.key_scores(Q, q_idx, K, 1, "dot"), O.key_scores(Q, q_idx, K, 1), atol=1e-12)
+    # the mean over queries never exceeds the max, and equals it for a single retained query
+    assert np.all(O.key_scores(Q, q_idx, K, 1, reduce="mean") <= O.key_scores(Q, q_idx, K, 1) + 1e-15)
+    one = O.select_queries(Q[:, :1], 4)
+    assert np.allclose(O.key_scores(Q[:, :1], one, K, 1, reduce="mean"), O.key_scores(Q[:, :1], one, K, 1), atol=1e-15)
