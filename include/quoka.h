@@ -21,7 +21,7 @@
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream).
  *     No call synchronises the host: QUOKA_OK means "validated and enqueued".
  *   - Argument problems are reported before anything is launched:
- *       QUOKA_EINVAL       null pointer, non-positive size, n_q_heads % n_kv_heads != 0, bad stride
+ *       QUOKA_EINVAL       null pointer, non-positive size, n_q_heads % n_kv_heads != 0, bad stride, unknown flag
  *       QUOKA_EUNSUPPORTED head_dim not in {64,128}, unknown dtype, size beyond a stated limit
  *       QUOKA_EWORKSPACE   workspace smaller than quoka_workspace_bytes() says (or misaligned)
  *       QUOKA_EHIP         the HIP runtime refused a launch
@@ -53,6 +53,13 @@ typedef enum {
 
 typedef enum { QUOKA_F32 = 0, QUOKA_BF16 = 1 } quoka_dtype;
 
+/* Ablation scorers (Sec. 3.2-3.3 and the appendix tables on scoring and aggregation); 0 is the method itself.
+ * They change quoka_select_queries' qbar and quoka_score_keys' scores only; the query sub-selection is the same. */
+enum {
+  QUOKA_SCORE_DOT = 1,  /* dot products instead of cosines: neither the retained queries nor the keys are normalised */
+  QUOKA_SCORE_MEAN = 2  /* mean instead of max over the retained-query axis                                          */
+};
+
 /* Problem description.  Notation of the paper: b, n_Q, n_KV, d, B_CP (chunk_len), T (kv length),
  * N_Q (n_retain), B_SA (budget). */
 typedef struct quoka_shape {
@@ -65,7 +72,7 @@ typedef struct quoka_shape {
   int32_t n_retain;     /* N_Q; N' = min(N_Q, C) queries are retained                         */
   int32_t max_budget;   /* B_max: extent of k_idx's last axis                                 */
   int32_t dtype;        /* quoka_dtype of Q, K, V, chunk K/V and O                            */
-  int32_t reserved;     /* must be 0                                                          */
+  int32_t score_flags;  /* 0, or QUOKA_SCORE_DOT | QUOKA_SCORE_MEAN (ablation scorers)        */
   int64_t q_stride[3];  /* Q        [b, n_Q,  C,     d]: batch, head, token strides (elements) */
   int64_t kv_stride[3]; /* K, V     [b, n_KV, T_max, d] (K and V share strides)               */
   int64_t ck_stride[3]; /* chunk KV [b, n_KV, C,     d] (chunk K and V share strides)         */
@@ -82,7 +89,8 @@ quoka_status quoka_workspace_bytes(const quoka_shape* shape, size_t* out_bytes);
  *   q_idx  out  [b, n_Q, N'] int32: retained chunk positions per q-head, ordered by ascending
  *               cosine to the head's mean query (ties: lower position first); 0..C-1 if C <= N_Q
  *   qbar   out  [b, n_KV, N', d] float32, dense: row r = mean over the heads of the KV group of the
- *               unit-normalised r-th retained query (norms clamped at 1e-8; not re-normalised)   */
+ *               unit-normalised r-th retained query (norms clamped at 1e-8; not re-normalised);
+ *               with QUOKA_SCORE_DOT the retained queries are averaged as they are              */
 quoka_status quoka_select_queries(const quoka_shape* shape, const void* q, int32_t* q_idx, float* qbar,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
@@ -92,6 +100,7 @@ quoka_status quoka_select_queries(const quoka_shape* shape, const void* q, int32
  *   kv_lens  in   [b] int32, 0 <= kv_lens[b] <= T_max
  *   scores   out  [b, n_KV, T_max] float32: scores[b,kv,t] = max_r <qbar[b,kv,r], K[b,kv,t]> /
  *                 max(||K[b,kv,t]||, 1e-8) for t < kv_lens[b]; entries t >= kv_lens[b] unspecified.
+ *                 QUOKA_SCORE_DOT drops the division, QUOKA_SCORE_MEAN replaces max_r by the mean over r.
  * The product is accumulated in float32; for bf16 keys Qbar enters as an exact three-term bf16 split. */
 quoka_status quoka_score_keys(const quoka_shape* shape, const float* qbar, const void* k_cache,
                               const int32_t* kv_lens, float* scores, void* workspace, size_t workspace_bytes,

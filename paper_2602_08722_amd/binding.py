@@ -37,7 +37,7 @@ class QuokaShape(ctypes.Structure):
         ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
         ("head_dim", ctypes.c_int32), ("chunk_len", ctypes.c_int32), ("max_kv_len", ctypes.c_int32),
         ("n_retain", ctypes.c_int32), ("max_budget", ctypes.c_int32), ("dtype", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("score_flags", ctypes.c_int32),
         ("q_stride", ctypes.c_int64 * 3), ("kv_stride", ctypes.c_int64 * 3),
         ("ck_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
     ]
@@ -99,8 +99,11 @@ def _strides3(t: torch.Tensor):
     return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
 
 
+QUOKA_SCORE_DOT, QUOKA_SCORE_MEAN = 1, 2   # ablation scorers (quoka.h)
+
+
 def make_shape(q: torch.Tensor, k_cache: torch.Tensor, k_chunk: torch.Tensor, out: torch.Tensor,
-               n_retain: int, max_budget: int) -> QuokaShape:
+               n_retain: int, max_budget: int, score_flags: int = 0) -> QuokaShape:
     """Describe the problem from the tensors' own shapes and strides (no copies)."""
     b, n_q, C, d = q.shape
     n_kv, t_max = k_cache.shape[1], k_cache.shape[2]
@@ -113,7 +116,7 @@ def make_shape(q: torch.Tensor, k_cache: torch.Tensor, k_chunk: torch.Tensor, ou
     s = QuokaShape()
     s.batch, s.n_q_heads, s.n_kv_heads, s.head_dim = b, n_q, n_kv, d
     s.chunk_len, s.max_kv_len, s.n_retain, s.max_budget = C, t_max, n_retain, max_budget
-    s.dtype, s.reserved = dt, 0
+    s.dtype, s.score_flags = dt, int(score_flags)
     s.q_stride = _strides3(q)
     if t_max > 0:
         s.kv_stride = _strides3(k_cache)
@@ -217,7 +220,8 @@ class PrefillBuffers:
 class ChunkBuffers:
     """Device buffers for one chunk-attention problem (allocation only; torch owns the memory)."""
 
-    def __init__(self, q, k_cache, v_cache, k_chunk, v_chunk, kv_lens, budgets, n_retain, max_budget=None):
+    def __init__(self, q, k_cache, v_cache, k_chunk, v_chunk, kv_lens, budgets, n_retain, max_budget=None,
+                 score_flags=0):
         dev = q.device
         b, n_q, C, d = q.shape
         n_kv, t_max = k_cache.shape[1], k_cache.shape[2]
@@ -227,7 +231,7 @@ class ChunkBuffers:
         if max_budget is None:
             max_budget = min(int(max(budgets)), t_max) if len(budgets) else 0
         self.out = torch.empty_like(q)
-        self.shape = make_shape(q, k_cache, k_chunk, self.out, n_retain, max_budget)
+        self.shape = make_shape(q, k_cache, k_chunk, self.out, n_retain, max_budget, score_flags)
         n_keep = self.shape.n_keep
         self.q_idx = torch.empty((b, n_q, n_keep), dtype=torch.int32, device=dev)
         self.qbar = torch.empty((b, n_kv, n_keep, d), dtype=torch.float32, device=dev)

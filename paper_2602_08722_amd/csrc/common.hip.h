@@ -19,6 +19,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // Kernel-side view of quoka_shape (plain copy; passed by value).
 struct Dims {
   int b, n_q, n_kv, g, d, C, T_max, n_ret, B_max;
+  int flags;   // QUOKA_SCORE_* bits
   long long qs[3], kvs[3], cks[3], os[3];
 };
 

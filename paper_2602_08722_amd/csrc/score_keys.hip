@@ -92,17 +92,23 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
   issue(0, RA);   // the first K tiles are in flight while the query operands are prepared
   if (n_tiles > 1) issue(1, RB);
 
+  const bool dot_mode = (dm.flags & 1) != 0, mean_mode = (dm.flags & 2) != 0;   // ablation scorers
   // Query operands: this wave's 32 query rows, split into three bf16 terms.
   bf16x8 a_hi[KS], a_mid[KS], a_lo[KS];
   {
     int r = qb * 32 + li;
-    r = r < n_keep ? r : n_keep - 1;  // padding rows repeat a real query: the max is unchanged
+    const bool pad_row = r >= n_keep;
+    r = pad_row ? n_keep - 1 : r;     // padding rows repeat a real query: the max is unchanged (the mean skips them)
     const float* qrow = qbar + ((size_t)(b * dm.n_kv + kv) * n_keep + r) * D + 8 * hf;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const float4 x0 = *reinterpret_cast<const float4*>(qrow + ks * 16);
       const float4 x1 = *reinterpret_cast<const float4*>(qrow + ks * 16 + 4);
-      const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+      float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+      if (mean_mode && pad_row) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = 0.f;
+      }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const __bf16 h = (__bf16)x[e];
@@ -124,8 +130,9 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
         const float* sm = smax + (it % 3) * QB * kScTile;
         float m = sm[tid];
 #pragma unroll
-        for (int j = 1; j < QB; ++j) m = fmaxf(m, sm[j * kScTile + tid]);
-        const float nrm = fmaxf(sqrtf(ssq[(it % 3) * kScTile + tid]), kNormEps);
+        for (int j = 1; j < QB; ++j) m = mean_mode ? m + sm[j * kScTile + tid] : fmaxf(m, sm[j * kScTile + tid]);
+        if (mean_mode) m /= (float)n_keep;
+        const float nrm = dot_mode ? 1.0f : fmaxf(sqrtf(ssq[(it % 3) * kScTile + tid]), kNormEps);
         sc[key] = m / nrm + 0.0f;
       }
     }
@@ -182,10 +189,18 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
       }
 #pragma unroll
       for (int u = 0; u < kPair; ++u) {
-        float m = -INFINITY;
+        float m;
+        if (mean_mode) {   // sum over this wave's 32 query rows (padding rows are zero)
+          m = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) m = fmaxf(m, c[u][v]);
-        m = fmaxf(m, other_half(m));
+          for (int v = 0; v < 16; ++v) m += c[u][v];
+          m += other_half(m);
+        } else {
+          m = -INFINITY;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) m = fmaxf(m, c[u][v]);
+          m = fmaxf(m, other_half(m));
+        }
         if (hf == 0) smax_g[qb * kScTile + kg * KPW + (kb + u) * 32 + li] = m;
       }
     }
@@ -223,15 +238,17 @@ __global__ __launch_bounds__(kScThreads) void score_f32(Dims dm, const float* __
     k[i] = x.x; k[i + 1] = x.y; k[i + 2] = x.z; k[i + 3] = x.w;
     ss += x.x * x.x; ss += x.y * x.y; ss += x.z * x.z; ss += x.w * x.w;
   }
-  float m = -INFINITY;
+  const bool dot_mode = (dm.flags & 1) != 0, mean_mode = (dm.flags & 2) != 0;   // ablation scorers
+  float m = mean_mode ? 0.f : -INFINITY;
   for (int r = 0; r < n_keep; ++r) {
     const float* qr = qs + r * D;
     float dot = 0.f;
 #pragma unroll
     for (int i = 0; i < D; ++i) dot += qr[i] * k[i];
-    m = fmaxf(m, dot);
+    m = mean_mode ? m + dot : fmaxf(m, dot);
   }
-  scores[(size_t)(b * dm.n_kv + kv) * dm.T_max + t] = m / fmaxf(sqrtf(ss), kNormEps) + 0.0f;
+  if (mean_mode) m /= (float)n_keep;
+  scores[(size_t)(b * dm.n_kv + kv) * dm.T_max + t] = m / (dot_mode ? 1.0f : fmaxf(sqrtf(ss), kNormEps)) + 0.0f;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -275,7 +275,7 @@ __global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, 
 #pragma unroll
       for (int e = 0; e < EPL; ++e) ss += v[jj][e] * v[jj][e];
       ss = wave64_sum(ss);
-      const float nrm = fmaxf(sqrtf(ss), kNormEps);
+      const float nrm = (dm.flags & 1) ? 1.0f : fmaxf(sqrtf(ss), kNormEps);   // dot-product ablation: no normalisation
       if (j0 + jj < dm.g) {   // wave-uniform; heads are accumulated in ascending order
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[e] += v[jj][e] / nrm;

@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(pk):
 def _shape(pk, **kw):
     s = pk.QuokaShape()
     vals = dict(batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128, chunk_len=64, max_kv_len=1000, n_retain=16,
-                max_budget=100, dtype=pk.QUOKA_BF16, reserved=0)
+                max_budget=100, dtype=pk.QUOKA_BF16, score_flags=0)
     vals.update(kw)
     for k, v in vals.items():
         setattr(s, k, v)
@@ -76,7 +76,7 @@ def test_workspace_query_and_status_strings(pk):
     (dict(chunk_len=0), 1),
     (dict(n_retain=0), 1),
     (dict(max_budget=2000), 1),                    # budget extent beyond the cache extent
-    (dict(reserved=3), 1),
+    (dict(score_flags=4), 1),
     (dict(head_dim=96), 2),
     (dict(dtype=7), 2),
     (dict(n_retain=129), 2),

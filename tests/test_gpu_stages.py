@@ -100,6 +100,55 @@ def test_score_keys(case):
     assert worst <= P.TOL_SCORE, f"max |score - oracle| = {worst}"
 
 
+ABLATION_CASES = [
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=256, n_retain=64, kv_lens=[1500]),
+    dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=256, n_retain=100, kv_lens=[4096 + 37]),   # padded query block
+    dict(dtype="bf16", n_q=4, n_kv=4, d=64, chunk=64, n_retain=40, kv_lens=[900]),
+    dict(dtype="f32", n_q=4, n_kv=2, d=128, chunk=64, n_retain=32, kv_lens=[300, 5], batch=2),
+]
+
+
+@pytest.mark.parametrize("flags", [1, 2, 3], ids=["dot", "mean", "dot+mean"])
+@pytest.mark.parametrize("case", ABLATION_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_ablation_scorers(case, flags):
+    """Sec. 3.2-3.3 ablations: dot product instead of cosine (bit 0), mean instead of max over queries (bit 1).
+    Q-bar and the scores are checked against the oracle's variants; the query sub-selection must not change."""
+    pk = _pk()
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    w = gen.make_custom(batch=batch, budgets=[8] * batch, seed=14, **case)
+    t = gen.to_torch(w, "cuda:0")
+    buf = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain,
+                          max_budget=min(8, w.t_max), score_flags=flags)
+    similarity = "dot" if flags & 1 else "cosine"
+    reduce = "mean" if flags & 2 else "max"
+    buf.select_queries()
+    buf.scores.fill_(float("nan"))
+    buf.score_keys()
+    torch.cuda.synchronize()
+    q_idx = gen.from_torch(buf.q_idx)
+    qbar = gen.from_torch(buf.qbar)
+    sc = gen.from_torch(buf.scores)
+    n_keep = min(w.n_retain, w.chunk)
+    for b in range(w.batch):
+        cos = O.cos_to_mean(w.Q[b])
+        for h in range(w.n_q):
+            P.check_query_ranking(q_idx[b, h], cos[h], n_keep, what=f"b{b} h{h}")
+        want_qbar = O.group_mean_queries(w.Q[b], q_idx[b], w.n_kv, similarity)
+        scale_q = max(1.0, float(np.abs(want_qbar).max()))
+        assert P.max_abs(qbar[b], want_qbar) <= P.TOL_QBAR * scale_q
+        T = w.kv_lens[b]
+        want = O.key_scores_preagg(qbar[b].astype(np.float64), w.K[b][:, :T], similarity, reduce)
+        got = sc[b, :, :T]
+        assert not np.isnan(got).any()
+        # dot products are not bounded by 1: the float32 accumulation error scales with the magnitudes involved
+        scale = max(1.0, float(np.abs(want).max())) if T > 0 else 1.0
+        assert P.max_abs(got, want) <= P.TOL_SCORE * scale * (4.0 if flags & 1 else 1.0)
+        # and the whole chain against the literal post-hoc form
+        lit = O.key_scores(w.Q[b], q_idx[b], w.K[b][:, :T], w.n_kv, similarity, reduce)
+        assert P.max_abs(got, lit) <= 4e-6 * scale * (4.0 if flags & 1 else 1.0)
+
+
 def _scores_for_topk(rng, n_kv, T, kind):
     if kind == "normal":
         return rng.standard_normal((n_kv, T)).astype(np.float32) * 0.2
