@@ -100,8 +100,11 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     n_cache = min(a.n_cache[b], dm.T_max);
   }
   n_cache = max(n_cache, 0);
+  // Tile order: the chunk's own tiles first, then the cache tiles.  The online softmax does not care, and the first
+  // chunk tile needs no index look-up and no cache length, so its loads leave right at kernel start.
+  const int n_cht = (c_end_blk + KT - 1) / KT;
   const int n_ct = (n_cache + KT - 1) / KT;
-  const int n_tiles = n_ct + (c_end_blk + KT - 1) / KT;
+  const int n_tiles = n_cht + n_ct;
 
   const uint16_t* qg = static_cast<const uint16_t*>(a.q);
   // The tensor this set stages (set 0: K, set 1: V) for this (batch, KV head), as byte pointers: every row is
@@ -136,8 +139,8 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
   do {                                                                                             \
     const int it_ = (IT);                                                                          \
     if (it_ < n_tiles) {                                                                           \
-      const bool cache_ = it_ < n_ct;                                                              \
-      const int base_ = cache_ ? it_ * KT : (it_ - n_ct) * KT;                                     \
+      const bool cache_ = it_ >= n_cht;                                                            \
+      const int base_ = cache_ ? (it_ - n_cht) * KT : it_ * KT;                                    \
       const int last_ = cache_ ? n_cache - 1 : C - 1;                                              \
       if (cache_ && sparse) {                                                                      \
         _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                                          \
@@ -152,15 +155,19 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
   } while (0)
 #define QUOKA_ISSUE(IT)                                                                            \
   do {                                                                                             \
-    const bool cache_ = (IT) < n_ct;                                                               \
+    const bool cache_ = (IT) >= n_cht;                                                             \
     const char* tb_ = cache_ ? cache_base : chunk_base;                                            \
     const uint32_t rb_ = cache_ ? cache_row_bytes : chunk_row_bytes;                               \
     _Pragma("unroll") for (int i = 0; i < NLD; ++i)                                                \
       R[i] = *reinterpret_cast<const u32x4*>(tb_ + (rows[i] * rb_ + (uint32_t)cg * 16u));          \
   } while (0)
 
-  QUOKA_RESOLVE(0);
-  QUOKA_ISSUE(0);   // n_tiles >= 1: the chunk is never empty
+  // tile 0 is the first chunk tile (the chunk is never empty): no index, no cache length
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    rows[i] = (uint32_t)min(r0 + RPI * i, C - 1);
+    R[i] = *reinterpret_cast<const u32x4*>(chunk_base + (rows[i] * chunk_row_bytes + (uint32_t)cg * 16u));
+  }
   QUOKA_RESOLVE(1);
 
   f32x16 o[DB];
@@ -175,12 +182,12 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
   f32x16 s[2];               // S^T of the tile between its two halves
 
   // first key (in the tile's own numbering: cache slot or chunk position) of this set's share of tile t
-  auto share_base = [&](int t) { return (t >= n_ct ? t - n_ct : t) * KT + sub; };
+  auto share_base = [&](int t) { return (t >= n_cht ? t - n_cht : t) * KT + sub; };
   // whether this wave has anything visible in its share of tile t
   auto computes = [&](int t) {
     if (!wave_on || t < 0 || t >= n_tiles) return false;
     const int base = share_base(t);
-    return t >= n_ct ? base <= tok0 + 31 : base < n_cache;
+    return t < n_cht ? base <= tok0 + 31 : base < n_cache;
   };
 
   // ---- first half of a tile: S^T = K Q^T ---------------------------------------------------------
@@ -201,7 +208,7 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
 
   // ---- second half: mask, online softmax, O^T += V^T P^T ---------------------------------------
   auto softmax_pv = [&](int t) __attribute__((always_inline)) {
-    const bool is_chunk = t >= n_ct;
+    const bool is_chunk = t < n_cht;
     const int base = share_base(t);
     const uint16_t* vt =
         reinterpret_cast<const uint16_t*>(smem + (size_t)(t & 1) * Cfg::kStageBytes + Cfg::kKTileBytes) + sub * LDV;
