@@ -20,6 +20,7 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct WsLayout {
   size_t select_off, select_bytes;
   size_t topk_off, topk_bytes;
+  size_t decode_off, decode_bytes;
   size_t total;
 };
 
@@ -71,7 +72,9 @@ WsLayout layout(const Dims& dm) {
   l.select_bytes = round_up(quoka::select_queries_ws_floats(dm) * sizeof(float), kAlign);
   l.topk_off = l.select_off + l.select_bytes;
   l.topk_bytes = round_up(quoka::topk_ws_words(dm) * sizeof(uint32_t), kAlign);
-  l.total = l.topk_off + l.topk_bytes;
+  l.decode_off = l.topk_off + l.topk_bytes;
+  l.decode_bytes = dm.b > 0 ? round_up(quoka::attn_decode_ws_floats(dm) * sizeof(float), kAlign) : 0;
+  l.total = l.decode_off + l.decode_bytes;
   if (l.total == 0) l.total = kAlign;
   return l;
 }
@@ -161,7 +164,8 @@ static quoka_status attn_common(const quoka_shape* shape, const void* q, const v
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_chunk) || !aligned16(v_chunk) ||
       !aligned16(out))
     return QUOKA_EINVAL;
-  st = check_ws(layout(dm), workspace, workspace_bytes);
+  const WsLayout l = layout(dm);
+  st = check_ws(l, workspace, workspace_bytes);
   if (st != QUOKA_OK) return st;
   quoka::AttnArgs a;
   a.q = q;
@@ -176,6 +180,10 @@ static quoka_status attn_common(const quoka_shape* shape, const void* q, const v
   a.out = out;
   a.lse = lse;
   hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (shape->dtype == QUOKA_BF16 && quoka::attn_decode_applies(dm)) {
+    float* part = reinterpret_cast<float*>(static_cast<char*>(workspace) + l.decode_off);
+    return from_hip(quoka::launch_attn_decode_bf16(dm, a, part, hs));
+  }
   return from_hip(shape->dtype == QUOKA_BF16 ? quoka::launch_attn_bf16(dm, a, hs) : quoka::launch_attn_f32(dm, a, hs));
 }
 

@@ -32,6 +32,10 @@ struct AttnArgs {
   float* lse;              // may be nullptr
 };
 hipError_t launch_attn_bf16(const Dims& dm, const AttnArgs& a, hipStream_t st);
+// decode-sized chunks (g * C <= 32 query rows per KV head): split-KV kernel + merge, partials in `part`
+bool attn_decode_applies(const Dims& dm);
+size_t attn_decode_ws_floats(const Dims& dm);
+hipError_t launch_attn_decode_bf16(const Dims& dm, const AttnArgs& a, float* part, hipStream_t st);
 hipError_t launch_attn_f32(const Dims& dm, const AttnArgs& a, hipStream_t st);
 
 }  // namespace quoka

@@ -72,6 +72,9 @@ E2E_CASES = [
     dict(dtype="bf16", n_q=4, n_kv=4, d=64, chunk=65, n_retain=65, kv_lens=[1000], budgets=[250]),
     dict(dtype="f32", n_q=4, n_kv=2, d=128, chunk=48, n_retain=8, kv_lens=[500, 33], budgets=[60, 20], batch=2),
     dict(dtype="bf16", n_q=16, n_kv=2, d=128, chunk=130, n_retain=128, kv_lens=[20000], budgets=[2400]),
+    # decode-sized chunks: every query is retained (C <= N_Q), attention runs on the split-KV kernel
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=1, n_retain=16, kv_lens=[4000], budgets=[480]),
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=4, n_retain=16, kv_lens=[2500, 0, 37], budgets=[300, 5, 37], batch=3),
 ]
 
 

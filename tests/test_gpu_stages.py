@@ -242,6 +242,13 @@ ATTN_CASES = [
     dict(dtype="bf16", n_q=16, n_kv=2, d=128, chunk=64, kv_lens=[256], budgets=[128]),      # group of 8
     dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=64, kv_lens=[0], budgets=[16]),          # empty cache
     dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=1, kv_lens=[200], budgets=[50]),         # single query
+    # decode-sized chunks (g * C <= 32): split-KV kernel
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=1, kv_lens=[5000], budgets=[1300]),      # several splits and tiles
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=8, kv_lens=[3000], budgets=[700]),       # 32 rows, causal chunk rows
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=5, kv_lens=[1, 0, 131], budgets=[1, 4, 128], batch=3),
+    dict(dtype="bf16", n_q=4, n_kv=4, d=64, chunk=32, kv_lens=[2000], budgets=[257]),       # group of 1, head_dim 64
+    dict(dtype="bf16", n_q=32, n_kv=2, d=128, chunk=2, kv_lens=[777], budgets=[100]),       # group of 16
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=9, kv_lens=[300], budgets=[64]),         # 36 rows: prefill kernel
     dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=80, kv_lens=[150, 0, 64], budgets=[40, 9, 64], batch=3),
     dict(dtype="f32", n_q=4, n_kv=2, d=64, chunk=20, kv_lens=[90, 0], budgets=[30, 5], batch=2),
 ]
