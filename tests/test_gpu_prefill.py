@@ -35,7 +35,7 @@ def _to_dev(x):
     return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).to("cuda:0")[None]
 
 
-@pytest.mark.parametrize("L,chunk", [(640, 128), (700, 192), (96, 128)])
+@pytest.mark.parametrize("L,chunk", [(640, 128), (700, 192), (96, 128), (130, 128), (1027, 256)])  # the last two end in a decode-sized chunk
 def test_dense_chunked_prefill_is_full_causal_attention(L, chunk):
     import paper_2602_08722_amd as pk
     pk.load_library()
@@ -47,7 +47,7 @@ def test_dense_chunked_prefill_is_full_causal_attention(L, chunk):
     assert P.max_abs(got, _full_causal(Q, K, V)) <= P.TOL_OUT["bf16"]
 
 
-@pytest.mark.parametrize("L,chunk,n_retain,budget", [(768, 128, 16, 96), (700, 192, 32, 64)])
+@pytest.mark.parametrize("L,chunk,n_retain,budget", [(768, 128, 16, 96), (700, 192, 32, 64), (1027, 256, 16, 200)])
 def test_sparse_chunked_prefill_matches_oracle(L, chunk, n_retain, budget):
     import paper_2602_08722_amd as pk
     pk.load_library()
