@@ -126,3 +126,24 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "library_path", lambda: str(tmp_path / "libquoka.so"))
     with pytest.raises(FileNotFoundError):
         B.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build is single-GPU: `bench.py --gpus N` with N > 1 must exit with a message, before touching a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2
+    assert "single-GPU" in r.stderr
+
+
+def test_product_path_never_touches_the_oracle():
+    """The package (binding, build script, kernels) must not import, read or link anything under oracle/."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2602_08722_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f), encoding="utf-8").read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
