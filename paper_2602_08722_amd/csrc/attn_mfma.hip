@@ -125,6 +125,12 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     const uint16_t* qrow = qg + b * dm.qs[0] + h * dm.qs[1] + (size_t)tokq * dm.qs[2] + 8 * hf;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
+    // The softmax scale and the change to base 2 go into Q once, so K Q^T arrives in the exponent's own units.
+    const float qscale = 1.4426950408889634f / sqrtf((float)D);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qreg[ks][e] = (__bf16)((float)qreg[ks][e] * qscale);
   }
 
   const int cg = tid % CG, r0 = tid / CG;
@@ -177,7 +183,11 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     for (int v = 0; v < 16; ++v) o[c][v] = 0.f;
   float m_run = -INFINITY;   // running row max, in the scaled log2 domain
   float l_run = 0.f;         // this half wave's share of the running row sum
-  const float sl2 = 1.4426950408889634f / sqrtf((float)D);
+  // -m_use in every entry: the accumulator K Q^T starts from, so the matrix core hands back s - m_use and the
+  // exponential needs no subtraction of its own.  Rewritten only when the reference point moves.
+  f32x16 cinit;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) cinit[v] = 0.f;
   const int tok = tok0 + li;
   f32x16 s[2];               // S^T of the tile between its two halves
 
@@ -195,13 +205,11 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     const uint16_t* kt = reinterpret_cast<const uint16_t*>(smem + (size_t)(t & 1) * Cfg::kStageBytes);
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
       const uint16_t* kp = kt + (sub + nb * 32 + li) * LD + 8 * hf;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 kop = *reinterpret_cast<const bf16x8*>(kp + ks * 16);
-        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[ks], s[nb], 0, 0, 0);
+        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[ks], ks == 0 ? cinit : s[nb], 0, 0, 0);
       }
     }
   };
@@ -229,24 +237,32 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
-    mx = fmaxf(mx, other_half(mx)) * sl2;
+    mx = fmaxf(mx, other_half(mx));   // relative to the reference point the tile was formed with
     constexpr float kLazy = 8.0f;
-    if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazy) != 0) {   // wave-uniform branch
-      const float m_new = (mx > m_run + kLazy) ? mx : m_run;       // -inf + 8 = -inf: the first visible tile lands here
+    const bool moves = m_run == -INFINITY ? mx > -INFINITY : mx > kLazy;
+    if (__builtin_amdgcn_ballot_w64(moves) != 0) {   // wave-uniform branch
+      const float m_old = (m_run == -INFINITY) ? 0.f : m_run;    // what the tile's scores are relative to
+      const float m_new = moves ? m_old + mx : m_run;
       const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_fin);
+      const float shift = m_fin - m_old;
       m_run = m_new;
       l_run *= alpha;
 #pragma unroll
       for (int c = 0; c < DB; ++c)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[c][v] *= alpha;
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[nb][v] -= shift;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) cinit[v] = -m_fin;
     }
-    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s[nb][v] = __builtin_amdgcn_exp2f(fmaf(s[nb][v], sl2, -m_use));
+      for (int v = 0; v < 16; ++v) s[nb][v] = __builtin_amdgcn_exp2f(s[nb][v]);
     // lane's corner of every transposing read: key 4*hf + (lane%16)/4, dims 16*((lane/16)%2) + 4*(lane%4)
     const tr_ptr vtr = (tr_ptr)(vt + (4 * hf + ((lane & 15) >> 2)) * LDV + 16 * ((lane >> 4) & 1) + 4 * (lane & 3));
     float psum = 0.f;
