@@ -57,7 +57,9 @@ typedef enum { QUOKA_F32 = 0, QUOKA_BF16 = 1 } quoka_dtype;
  * They change quoka_select_queries' qbar and quoka_score_keys' scores only; the query sub-selection is the same. */
 enum {
   QUOKA_SCORE_DOT = 1,  /* dot products instead of cosines: neither the retained queries nor the keys are normalised */
-  QUOKA_SCORE_MEAN = 2  /* mean instead of max over the retained-query axis                                          */
+  QUOKA_SCORE_MEAN = 2, /* mean instead of max over the retained-query axis                                          */
+  QUOKA_SELECT_UNIFORM = 4 /* uniformly sampled queries (the query-sampling baseline of Sec. 4) instead of the lowest
+                              cosines: positions floor(r * C / N_Q), r = 0..N_Q-1, the same for every head           */
 };
 
 /* Problem description.  Notation of the paper: b, n_Q, n_KV, d, B_CP (chunk_len), T (kv length),
@@ -72,7 +74,7 @@ typedef struct quoka_shape {
   int32_t n_retain;     /* N_Q; N' = min(N_Q, C) queries are retained                         */
   int32_t max_budget;   /* B_max: extent of k_idx's last axis                                 */
   int32_t dtype;        /* quoka_dtype of Q, K, V, chunk K/V and O                            */
-  int32_t score_flags;  /* 0, or QUOKA_SCORE_DOT | QUOKA_SCORE_MEAN (ablation scorers)        */
+  int32_t score_flags;  /* 0, or an OR of QUOKA_SCORE_DOT, QUOKA_SCORE_MEAN, QUOKA_SELECT_UNIFORM */
   int64_t q_stride[3];  /* Q        [b, n_Q,  C,     d]: batch, head, token strides (elements) */
   int64_t kv_stride[3]; /* K, V     [b, n_KV, T_max, d] (K and V share strides)               */
   int64_t ck_stride[3]; /* chunk KV [b, n_KV, C,     d] (chunk K and V share strides)         */
@@ -87,7 +89,8 @@ quoka_status quoka_workspace_bytes(const quoka_shape* shape, size_t* out_bytes);
  * group mean; Sec. 3.1 and 3.3).
  *   q      in   [b, n_Q, C, d] (shape.dtype)
  *   q_idx  out  [b, n_Q, N'] int32: retained chunk positions per q-head, ordered by ascending
- *               cosine to the head's mean query (ties: lower position first); 0..C-1 if C <= N_Q
+ *               cosine to the head's mean query (ties: lower position first); 0..C-1 if C <= N_Q;
+ *               with QUOKA_SELECT_UNIFORM (and C > N_Q) the positions floor(r * C / N_Q) in ascending order
  *   qbar   out  [b, n_KV, N', d] float32, dense: row r = mean over the heads of the KV group of the
  *               unit-normalised r-th retained query (norms clamped at 1e-8; not re-normalised);
  *               with QUOKA_SCORE_DOT the retained queries are averaged as they are              */

@@ -55,17 +55,27 @@ def cos_to_mean(Q: np.ndarray) -> np.ndarray:
     return dots / (qn * mn[:, None])
 
 
-def select_queries(Q: np.ndarray, n_retain: int) -> np.ndarray:
-    """Indices of the retained queries per q-head, in rank order.
+def select_queries(Q: np.ndarray, n_retain: int, rule: str = "cosine") -> np.ndarray:
+    """Indices of the retained queries per q-head.
 
     Alg. 1: only when the chunk is longer than N_Q, keep the N_Q queries that
-    rank highest by -CosSim(M_Q, q), i.e. the lowest cosines; otherwise keep all
-    queries in position order.
+    rank highest by -CosSim(M_Q, q), i.e. the lowest cosines, in rank order;
+    otherwise keep all queries in position order.
+
+    rule="uniform" is the query-sampling baseline the experiments compare with
+    (Sec. 4, sparse attention baselines: queries sampled uniformly): the N_Q
+    positions floor(r * C / N_Q), r = 0..N_Q-1, the same for every head.  The
+    paper does not say how the uniform sample is drawn; an even stride is the
+    deterministic form of it (reading listed in the design notes).
     """
+    assert rule in ("cosine", "uniform")
     Q = np.asarray(Q, dtype=np.float64)
     n_q, C, _ = Q.shape
     if C <= n_retain:
         return np.tile(np.arange(C, dtype=np.int64), (n_q, 1))
+    if rule == "uniform":
+        pos = [(r * C) // n_retain for r in range(n_retain)]
+        return np.tile(np.asarray(pos, dtype=np.int64), (n_q, 1))
     s = cos_to_mean(Q)
     order = np.argsort(s, axis=1, kind="stable")  # ascending cosine, ties -> lower index
     return order[:, :n_retain].astype(np.int64)
@@ -231,11 +241,12 @@ def dense_attn(Q, K, V, Kc, Vc, return_lse: bool = False, rows=None, heads=None)
     return sparse_attn(Q, K, V, full, Kc, Vc, return_lse, rows, heads)
 
 
-def quoka_select(Q, K, n_retain: int, budget: int, similarity: str = "cosine", reduce: str = "max"):
-    """Alg. 1 up to the index set: returns (q_idx, scores, k_idx).  The query sub-selection is the same for the
-    ablation scorers; only the key scores change."""
+def quoka_select(Q, K, n_retain: int, budget: int, similarity: str = "cosine", reduce: str = "max",
+                 query_rule: str = "cosine"):
+    """Alg. 1 up to the index set: returns (q_idx, scores, k_idx).  The ablation scorers change only the key
+    scores; query_rule="uniform" changes only which queries are retained."""
     n_kv = np.asarray(K).shape[0]
-    q_idx = select_queries(Q, n_retain)
+    q_idx = select_queries(Q, n_retain, query_rule)
     scores = key_scores(Q, q_idx, K, n_kv, similarity, reduce)
     k_idx = topk_keys(scores, budget)
     return q_idx, scores, k_idx

@@ -241,6 +241,13 @@ __global__ void sq_identity(Dims dm, int32_t* __restrict__ q_idx, int n_keep) {
   for (int i = threadIdx.x; i < n_keep; i += blockDim.x) q_idx[(size_t)(b * dm.n_q + h) * n_keep + i] = i;
 }
 
+// Uniform query sampling (the query-sampling baseline of Sec. 4): an even stride over the chunk, no look at the data.
+__global__ void sq_uniform(Dims dm, int32_t* __restrict__ q_idx, int n_keep) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  for (int r = threadIdx.x; r < n_keep; r += blockDim.x)
+    q_idx[(size_t)(b * dm.n_q + h) * n_keep + r] = (int32_t)(((int64_t)r * dm.C) / n_keep);
+}
+
 // ---------------------------------------------------------------------------------------------
 // One wave per (r, kv, b): lanes own D/64 consecutive elements each.  The group's rows are all requested before
 // any is used, so the kernel pays one index latency and one row latency, not g of each.
@@ -293,7 +300,9 @@ static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, fl
                                float* ws_cos, hipStream_t st) {
   const int n_keep = dm.n_ret < dm.C ? dm.n_ret : dm.C;
   const T* qp = static_cast<const T*>(q);
-  if (dm.C > dm.n_ret) {
+  if (dm.C > dm.n_ret && (dm.flags & QUOKA_SELECT_UNIFORM)) {
+    hipLaunchKernelGGL(sq_uniform, dim3(dm.n_q, dm.b), dim3(64), 0, st, dm, q_idx, n_keep);
+  } else if (dm.C > dm.n_ret) {
     const int n_tiles = (dm.C + kSqTile - 1) / kSqTile;
     dim3 grid(n_tiles, dm.n_q, dm.b);
     hipLaunchKernelGGL((sq_partial_sums<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, n_tiles);

@@ -149,6 +149,45 @@ def test_ablation_scorers(case, flags):
         assert P.max_abs(got, lit) <= 4e-6 * scale * (4.0 if flags & 1 else 1.0)
 
 
+@pytest.mark.parametrize("flags", [4, 7], ids=["uniform", "uniform+dot+mean"])
+@pytest.mark.parametrize("case", ABLATION_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_uniform_query_sampling(case, flags):
+    """The query-sampling baseline of Sec. 4 (queries sampled uniformly): q_idx is the even stride, bit-exact, and
+    everything downstream (Q-bar, scores, selected keys, attention output) follows the oracle run with that rule."""
+    pk = _pk()
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    budgets = [max(1, t // 5) for t in case["kv_lens"]]
+    w = gen.make_custom(batch=batch, budgets=budgets, seed=15, **case)
+    t = gen.to_torch(w, "cuda:0")
+    buf = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain,
+                          score_flags=flags)
+    similarity = "dot" if flags & 1 else "cosine"
+    reduce = "mean" if flags & 2 else "max"
+    buf.q_idx.fill_(-1)
+    buf.chunk_attn()
+    torch.cuda.synchronize()
+    q_idx, qbar, sc = gen.from_torch(buf.q_idx), gen.from_torch(buf.qbar), gen.from_torch(buf.scores)
+    k_idx, k_cnt, out = gen.from_torch(buf.k_idx), gen.from_torch(buf.k_cnt), gen.from_torch(buf.out)
+    tol_out = P.TOL_OUT[w.dtype]
+    for b in range(w.batch):
+        T, B = w.kv_lens[b], w.budgets[b]
+        want_idx, want_sc, _ = O.quoka_select(w.Q[b], w.K[b][:, :T], w.n_retain, B, similarity, reduce, "uniform")
+        assert np.array_equal(q_idx[b], want_idx)
+        assert P.max_abs(qbar[b], O.group_mean_queries(w.Q[b], want_idx, w.n_kv, similarity)) <= \
+            P.TOL_QBAR * max(1.0, float(np.abs(w.Q[b]).max()) if flags & 1 else 1.0)
+        scale = max(1.0, float(np.abs(want_sc).max()))
+        assert P.max_abs(sc[b, :, :T], want_sc) <= 4e-6 * scale * (4.0 if flags & 1 else 1.0)
+        sel = []
+        for kv in range(w.n_kv):
+            n = int(k_cnt[b, kv])
+            assert n == min(B, T)
+            P.check_topk_set(k_idx[b, kv, :n], want_sc[kv], B, what=f"b{b} kv{kv}")
+            sel.append(k_idx[b, kv, :n])
+        want_out = O.sparse_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], np.stack(sel), w.Kc[b], w.Vc[b])
+        assert P.max_abs(out[b], want_out) <= tol_out
+
+
 def _scores_for_topk(rng, n_kv, T, kind):
     if kind == "normal":
         return rng.standard_normal((n_kv, T)).astype(np.float32) * 0.2

@@ -117,3 +117,47 @@ def test_theorem1_inequality_holds_for_arbitrary_vectors(seed, d):
     c = O.cos_to_mean(Q)[0, 0]
     assert c == pytest.approx(cs(M, q), abs=1e-10)
     assert c <= 1 + a * b - 0.5 * a * a - 0.5 * b * b + 1e-10
+
+
+# ---- uniform query sampling (the query-sampling baseline of Sec. 4) -----------------------------------------
+def test_uniform_rule_is_an_even_stride_independent_of_the_data():
+    # C a multiple of N_Q: exactly every (C / N_Q)-th position, starting at 0
+    Q = _rand(7, 3, 32, 4)
+    idx = O.select_queries(Q, 8, rule="uniform")
+    assert idx.tolist() == [[0, 4, 8, 12, 16, 20, 24, 28]] * 3
+    # the sample does not look at the values
+    assert np.array_equal(idx, O.select_queries(-5.0 * Q[::-1], 8, rule="uniform"))
+
+
+@pytest.mark.parametrize("C,n", [(10, 3), (11, 4), (97, 16), (1024, 64), (129, 128)])
+def test_uniform_rule_ragged_stride_properties(C, n):
+    # positions strictly increase, start at 0, stay inside the chunk, and consecutive gaps are floor or ceil of C/n
+    idx = O.select_queries(np.ones((1, C, 2)), n, rule="uniform")[0]
+    assert idx[0] == 0 and idx[-1] < C and len(idx) == n
+    gaps = np.diff(idx)
+    assert gaps.min() >= C // n >= 1 and gaps.max() <= -(-C // n)
+    # sample r is the last integer point not beyond r*C/n (integer form of the inequality, no rounding involved)
+    for r in range(n):
+        assert int(idx[r]) * n <= r * C < (int(idx[r]) + 1) * n
+
+
+def test_uniform_rule_keeps_everything_for_short_chunks():
+    assert O.select_queries(_rand(8, 2, 5, 3), 5, rule="uniform").tolist() == [[0, 1, 2, 3, 4]] * 2
+
+
+def test_uniform_rule_feeds_the_same_scoring_as_an_explicit_index_list():
+    Q, K = _rand(9, 4, 24, 8), _rand(10, 2, 40, 8)
+    q_idx, scores, k_idx = O.quoka_select(Q, K, 6, 10, query_rule="uniform")
+    assert q_idx.tolist() == [[0, 4, 8, 12, 16, 20]] * 4
+    # brute force: group mean of cosines with the strided queries, max over them
+    for kv in range(2):
+        for t in range(40):
+            best = -np.inf
+            for r in range(6):
+                c = 0.0
+                for j in range(2):
+                    qv = Q[2 * kv + j, 4 * r]
+                    c += 1.0 - scipy_cosine_distance(qv, K[kv, t])
+                best = max(best, c / 2)
+            assert abs(scores[kv, t] - best) < 1e-12
+    assert np.array_equal(k_idx, O.topk_keys(scores, 10))
