@@ -254,13 +254,9 @@ __global__ __launch_bounds__(kDcThreads) void attn_decode_merge(Dims dm, AttnArg
     l_s = base[tid * sstride + 1];
   }
   if (tid < 64) {   // n_splits <= 64: one wave holds all of them
-    float m = m_s;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, kWave));
+    const float m = wave64_max(m_s);
     const float w = (m_s == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_s - m);
-    float l = w * l_s;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o, kWave);
+    const float l = wave64_sum(w * l_s);
     if (tid < n_splits) wgt[tid] = w;
     if (tid == 0) {
       s_m = m;

@@ -88,12 +88,59 @@ __device__ __forceinline__ float row16_sum(float x) {
   return x;
 }
 
-// Sum over the 64 lanes of a wave: DPP inside each 16-lane row, then two cross-row exchanges.
-__device__ __forceinline__ float wave64_sum(float x) {
-  x = row16_sum(x);
-  x += __shfl_xor(x, 16, kWave);
-  x += __shfl_xor(x, 32, kWave);
+// Cross-lane steps on the VALU's DPP path (no LDS crossbar, a few clocks each instead of a ds_bpermute round trip).
+// CTRL: row_shr:n = 0x110 + n (lane i reads lane i-n of its 16-lane row), row_bcast:15 = 0x142 (lane 15 of every row to
+// the next row), row_bcast:31 = 0x143 (lane 31 to rows 2 and 3).  A lane without a source, or in a row that ROW_MASK
+// leaves out, gets `idle`.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp_take(uint32_t idle, uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)idle, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+
+// Inclusive scan over the 64 lanes with OP (associative; IDLE its neutral element's bit pattern): four shifted steps
+// inside each row, then the row totals travel down.  Lane 63 ends with the reduction over the wave.
+#define QUOKA_WAVE_SCAN(x, OP, IDLE)                                   \
+  do {                                                                 \
+    x = OP(x, dpp_take<0x111>(IDLE, x));                               \
+    x = OP(x, dpp_take<0x112>(IDLE, x));                               \
+    x = OP(x, dpp_take<0x114>(IDLE, x));                               \
+    x = OP(x, dpp_take<0x118>(IDLE, x));                               \
+    x = OP(x, dpp_take<0x142, 0xA>(IDLE, x));                          \
+    x = OP(x, dpp_take<0x143, 0xC>(IDLE, x));                          \
+  } while (0)
+
+__device__ __forceinline__ uint32_t op_add_u32(uint32_t a, uint32_t b) { return a + b; }
+__device__ __forceinline__ uint32_t op_min_u32(uint32_t a, uint32_t b) { return a < b ? a : b; }
+__device__ __forceinline__ uint32_t op_max_u32(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t op_add_f32(uint32_t a, uint32_t b) {
+  return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
+}
+__device__ __forceinline__ uint32_t op_max_f32(uint32_t a, uint32_t b) {
+  return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b)));
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t x) {
+  QUOKA_WAVE_SCAN(x, op_add_u32, 0u);
   return x;
+}
+// Reductions over the wave; every lane gets the result (read from lane 63 into a scalar register).
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
+  QUOKA_WAVE_SCAN(x, op_min_u32, 0xFFFFFFFFu);
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+  QUOKA_WAVE_SCAN(x, op_max_u32, 0u);
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+__device__ __forceinline__ float wave64_sum(float xf) {
+  uint32_t x = __float_as_uint(xf);
+  QUOKA_WAVE_SCAN(x, op_add_f32, 0u);
+  return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)x, 63));
+}
+__device__ __forceinline__ float wave64_max(float xf) {
+  uint32_t x = __float_as_uint(xf);
+  QUOKA_WAVE_SCAN(x, op_max_f32, 0xFF800000u);   // -inf
+  return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)x, 63));
 }
 
 // Exchange between lane l and lane l^32 through v_permlane32_swap: returns the partner's value.
@@ -110,23 +157,13 @@ __device__ __forceinline__ float other_half(float x) {
 template <int NT>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t x, uint32_t* wsum, uint32_t* total) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  uint32_t inc = x;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t y = __shfl_up(inc, o, kWave);
-    if (lane >= o) inc += y;
-  }
+  const uint32_t inc = wave_incl_scan_u32(x);
   __syncthreads();  // protect wsum against a previous use
   if (lane == 63) wsum[w] = inc;
   __syncthreads();
   if (w == 0) {   // wave 0 scans the NT/64 wave totals
     const uint32_t t = lane < NT / 64 ? wsum[lane] : 0u;
-    uint32_t run = t;
-#pragma unroll
-    for (int o = 1; o < NT / 64; o <<= 1) {
-      const uint32_t y = __shfl_up(run, o, kWave);
-      if (lane >= o) run += y;
-    }
+    const uint32_t run = wave_incl_scan_u32(t);
     if (lane < NT / 64) wsum[lane] = run - t;
     if (lane == NT / 64 - 1) wsum[NT / 64] = run;
   }
@@ -135,41 +172,93 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t x, uint32_t* wsum, 
   return wsum[w] + inc - x;
 }
 
-// One wave (the caller guarantees threadIdx.x < 64 and all 64 lanes active) walks a 256-bin LDS
-// histogram in descending (DESC) or ascending bin order and finds the bin in which the running count
-// reaches `need` (1-based rank, need <= total count).  The one lane that finds it ORs the bin, shifted,
-// into *prefix_io and stores the rank remaining inside the bin to *need_out.
-template <bool DESC>
-__device__ __forceinline__ void wave_find_bin256(const uint32_t* hist, uint32_t need, int shift, uint32_t* prefix_io,
-                                                 uint32_t* need_out) {
-  const int lane = threadIdx.x & 63;
-  uint32_t c[4];
-  uint32_t sum = 0;
+// Block-wide radix select over keys held in registers (blocks of 1024 threads, every thread calls it).
+// key[j] is an order-preserving uint32 image; bit j of `valid` says whether key[j] is a real element.  Finds the key
+// of the element of rank `need` (1-based; counted from the largest if DESC, else from the smallest; the caller
+// guarantees need <= number of valid elements) and how many elements equal to that key belong to the first `need`.
+// 8 bits per pass, starting below the leading bits that all valid keys share (scores of one head sit in a narrow
+// range and would otherwise pile into one or two bins of the first passes).  One block barrier per pass: the
+// histograms rotate through three LDS buffers (the buffer of pass p is cleared during pass p+2's predecessor), and
+// every wave locates the cut bin for itself from the finished histogram, so nothing is handed around through LDS.
+struct RadixSelectLds {
+  uint32_t hist[3][256];
+  uint32_t wmin[16], wmax[16];
+};
+
+template <int IPT, bool DESC>
+__device__ __forceinline__ void block_radix_select(const uint32_t (&key)[IPT], uint32_t valid, uint32_t need,
+                                                   RadixSelectLds& L, uint32_t* cut_key, uint32_t* need_eq) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid < 768) (&L.hist[0][0])[tid] = 0u;
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int o = 4 * lane + j;   // position in scan order
-    c[j] = hist[DESC ? 255 - o : o];
-    sum += c[j];
-  }
-  uint32_t inc = sum;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t y = __shfl_up(inc, o, kWave);
-    if (lane >= o) inc += y;
-  }
-  const uint32_t excl = inc - sum;
-  if (excl < need && need <= inc) {   // exactly one lane
-    uint32_t rem = need - excl;
-    int j = 0;
-#pragma unroll
-    for (; j < 3; ++j) {
-      if (rem <= c[j]) break;
-      rem -= c[j];
+  for (int j = 0; j < IPT; ++j) {
+    if ((valid >> j) & 1u) {
+      kmin = min(kmin, key[j]);
+      kmax = max(kmax, key[j]);
     }
-    const int o = 4 * lane + j;
-    *prefix_io |= (uint32_t)(DESC ? 255 - o : o) << shift;
-    *need_out = rem;
   }
+  kmin = wave_min_u32(kmin);
+  kmax = wave_max_u32(kmax);
+  if (lane == 0) {
+    L.wmin[w] = kmin;
+    L.wmax[w] = kmax;
+  }
+  __syncthreads();
+  kmin = wave_min_u32(lane < 16 ? L.wmin[lane] : 0xFFFFFFFFu);
+  kmax = wave_max_u32(lane < 16 ? L.wmax[lane] : 0u);
+  const uint32_t diff = kmin ^ kmax;
+  int hi = diff ? 32 - __clz(diff) : 0;                                    // valid keys agree on all bits >= hi
+  uint32_t mask = hi >= 32 ? 0u : ~((hi == 0) ? 0u : ((1u << hi) - 1u));   // decided bits
+  uint32_t prefix = kmax & mask;                                           // (kmin and kmax agree there)
+  uint32_t* h_use = L.hist[0];
+  uint32_t* h_next = L.hist[1];
+  uint32_t* h_clear = L.hist[2];
+  bool first = true;
+  while (hi > 0) {
+    const int lo_bit = max(hi - 8, 0);
+    const uint32_t dmask = (1u << (hi - lo_bit)) - 1u;
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const uint32_t k = key[j];
+      if (((valid >> j) & 1u) && (k & mask) == prefix) atomicAdd(&h_use[(k >> lo_bit) & dmask], 1u);
+    }
+    __syncthreads();
+    // h_clear was last read before this barrier (during the previous pass) and is next written after the next one
+    if (!first && tid < 256) h_clear[tid] = 0u;
+    first = false;
+    // scan order position o = 4*lane + i is bin 255-o (DESC) or o
+    const u32x4 raw = *reinterpret_cast<const u32x4*>(h_use + 4 * (DESC ? 63 - lane : lane));
+    uint32_t c[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c[i] = DESC ? raw[3 - i] : raw[i];
+    const uint32_t sum = c[0] + c[1] + c[2] + c[3];
+    const uint32_t inc = wave_incl_scan_u32(sum);
+    const uint32_t excl = inc - sum;
+    const bool hit = excl < need && need <= inc;   // exactly one lane
+    uint32_t rem = need - excl;
+    int i = 0;
+#pragma unroll
+    for (; i < 3; ++i) {
+      if (rem <= c[i]) break;
+      rem -= c[i];
+    }
+    const int o = 4 * lane + i;
+    const unsigned long long bal = __builtin_amdgcn_ballot_w64(hit);
+    if (bal == 0) break;   // cannot happen while need <= number of valid elements
+    const int src = __builtin_ctzll(bal);
+    const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane(DESC ? 255 - o : o, src);
+    need = (uint32_t)__builtin_amdgcn_readlane((int)rem, src);
+    prefix |= bin << lo_bit;
+    mask |= dmask << lo_bit;
+    hi = lo_bit;
+    uint32_t* t = h_use;
+    h_use = h_next;
+    h_next = h_clear;
+    h_clear = t;
+  }
+  *cut_key = prefix;
+  *need_eq = need;
 }
 
 }  // namespace quoka

@@ -121,10 +121,9 @@ template <int IPT>
 __global__ __launch_bounds__(kSelThreads) void sq_select(Dims dm, const float* __restrict__ cosv,
                                                         int32_t* __restrict__ q_idx, int n_keep) {
   constexpr int NW = kSelThreads / 64;
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t s_prefix, s_need, n_sel;
+  __shared__ RadixSelectLds rs;
+  __shared__ uint32_t n_sel;
   __shared__ uint32_t wsum[NW + 1];
-  __shared__ uint32_t wmin[NW], wmax[NW];
   __shared__ uint32_t sel_key[kMaxKeep];
   __shared__ uint32_t sel_idx[kMaxKeep];
   const int h = blockIdx.x, b = blockIdx.y;
@@ -133,60 +132,17 @@ __global__ __launch_bounds__(kSelThreads) void sq_select(Dims dm, const float* _
   const float* cv = cosv + (size_t)(b * dm.n_q + h) * C;
   const int lo = tid * IPT;
   uint32_t key[IPT];
-  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  uint32_t valid = 0u;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
-    key[j] = lo + j < C ? okey(cv[lo + j]) : 0xFFFFFFFFu;
-    if (lo + j < C) {
-      kmin = min(kmin, key[j]);
-      kmax = max(kmax, key[j]);
-    }
+    const bool in = lo + j < C;
+    key[j] = in ? okey(cv[lo + j]) : 0xFFFFFFFFu;
+    valid |= (in ? 1u : 0u) << j;
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
-  }
-  if (lane == 0) {
-    wmin[w] = kmin;
-    wmax[w] = kmax;
-  }
-  __syncthreads();
-  kmin = wmin[0];
-  kmax = wmax[0];
-#pragma unroll
-  for (int i = 1; i < NW; ++i) {
-    kmin = min(kmin, wmin[i]);
-    kmax = max(kmax, wmax[i]);
-  }
-  const uint32_t diff = kmin ^ kmax;
-  int hi = diff ? 32 - __clz(diff) : 0;                                    // keys agree on all bits >= hi
-  uint32_t mask = hi >= 32 ? 0u : ~((hi == 0) ? 0u : ((1u << hi) - 1u));   // decided bits
-  if (tid == 0) {
-    s_prefix = kmin & mask;
-    s_need = (uint32_t)n_keep;   // rank (1-based, ascending) of the cut element
-    n_sel = 0;
-  }
-  __syncthreads();
-  while (hi > 0) {
-    const int lo_bit = max(hi - 8, 0);
-    const uint32_t dmask = (1u << (hi - lo_bit)) - 1u;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    const uint32_t prefix = s_prefix;
-#pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-      const uint32_t k = key[j];
-      if (lo + j < C && (k & mask) == prefix) atomicAdd(&hist[(k >> lo_bit) & dmask], 1u);
-    }
-    __syncthreads();
-    if (tid < 64) wave_find_bin256<false>(hist, s_need, lo_bit, &s_prefix, &s_need);   // ascending: smallest
-    mask |= dmask << lo_bit;
-    hi = lo_bit;
-    __syncthreads();
-  }
-  const uint32_t tau = s_prefix;      // key of the n_keep-th smallest cosine
-  const uint32_t need_eq = s_need;    // how many elements equal to tau are kept (lowest positions first)
+  if (tid == 0) n_sel = 0;
+  // tau: key of the n_keep-th smallest cosine; need_eq: how many elements equal to it are kept (lowest positions first)
+  uint32_t tau, need_eq;
+  block_radix_select<IPT, false>(key, valid, (uint32_t)n_keep, rs, &tau, &need_eq);
   uint32_t c_eq = 0;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) c_eq += (lo + j < C) && (key[j] == tau);

@@ -14,7 +14,7 @@
 
 namespace quoka {
 
-constexpr int kSmallMax = 32768;   // beyond this one compute unit's LDS atomics are slower than the multi-block path
+constexpr int kSmallMax = 32768;   // beyond this one compute unit is slower than the multi-block path
 constexpr int kSmallThreads = 1024;
 constexpr int kLgThreads = 256;
 constexpr int kLgTile = 2048;          // scores per block in the multi-block path
@@ -26,10 +26,9 @@ __device__ __forceinline__ uint32_t radix_bins(int pass) { return pass == 2 ? 10
 // ---------------------------------------------------------------------------------------------
 // Single-block path.  Wave w owns scores [w*64*IPT, (w+1)*64*IPT); its register j of lane l is score
 // w*64*IPT + 64*j + l, so every load is a coalesced 256-byte row and position order inside a wave is (j, lane).
-// The radix select (8 bits per pass, LDS histogram) skips the leading bits that all keys share: scores of one head
-// usually sit in a narrow range, which would otherwise pile every key into one or two bins of the first passes.
-// The ordered compaction needs no scan over threads: per register, two wave ballots give every lane the number of
-// earlier taken positions of its wave, and the 16 wave totals are combined through LDS.
+// The cut key comes from the block-wide radix select; the ordered compaction needs no scan over threads: per
+// register, two wave ballots give every lane the number of earlier taken positions of its wave, and the 16 wave
+// totals are combined through LDS.
 
 template <int IPT>
 __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float* __restrict__ scores,
@@ -37,12 +36,17 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
                                                            const int32_t* __restrict__ budgets,
                                                            int32_t* __restrict__ k_idx, int32_t* __restrict__ k_cnt) {
   constexpr int NW = kSmallThreads / 64;
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t s_prefix, s_need;
-  __shared__ uint32_t wmin[NW], wmax[NW];
+  __shared__ RadixSelectLds rs;
   __shared__ uint32_t wgt[NW], weq[NW];
   const int kv = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const float* sc = scores + (size_t)(b * dm.n_kv + kv) * dm.T_max;
+  const int lo = w * 64 * IPT + lane;   // position of register 0; register j is 64*j further
+  // The scores are requested before the cache length is known (the row has T_max entries; those past the length
+  // are discarded below), so the two fetches overlap instead of queueing behind each other.
+  float raw[IPT];
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) raw[j] = lo + 64 * j < dm.T_max ? sc[lo + 64 * j] : 0.f;
   const int T = max(0, min(kv_lens[b], dm.T_max));
   const int B = max(0, min(min(budgets[b], T), dm.B_max));
   int32_t* out = k_idx + (size_t)(b * dm.n_kv + kv) * dm.B_max;
@@ -52,68 +56,21 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
     for (int i = tid; i < T; i += kSmallThreads) out[i] = i;
     return;
   }
-  const float* sc = scores + (size_t)(b * dm.n_kv + kv) * dm.T_max;
-  const int lo = w * 64 * IPT + lane;   // position of register 0; register j is 64*j further
   uint32_t key[IPT];
-  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  uint32_t valid = 0u;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
-    const int t = lo + 64 * j;
-    // padding key 0 sorts below the image of every real score, so it is never selected (B < T)
-    key[j] = t < T ? okey(sc[t]) : 0u;
-    if (t < T) {
-      kmin = min(kmin, key[j]);
-      kmax = max(kmax, key[j]);
-    }
+    const bool in = lo + 64 * j < T;
+    key[j] = in ? okey(raw[j]) : 0u;
+    valid |= (in ? 1u : 0u) << j;
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
-  }
-  if (lane == 0) {
-    wmin[w] = kmin;
-    wmax[w] = kmax;
-  }
-  __syncthreads();
-  kmin = wmin[0];
-  kmax = wmax[0];
-#pragma unroll
-  for (int i = 1; i < NW; ++i) {
-    kmin = min(kmin, wmin[i]);
-    kmax = max(kmax, wmax[i]);
-  }
-  const uint32_t diff = kmin ^ kmax;
-  int hi = diff ? 32 - __clz(diff) : 0;                       // keys agree on all bits >= hi
-  uint32_t mask = hi >= 32 ? 0u : ~((hi == 0) ? 0u : ((1u << hi) - 1u));   // decided bits
-  if (tid == 0) {
-    s_prefix = kmax & mask;
-    s_need = (uint32_t)B;   // rank (1-based, descending) of the cut element
-  }
-  __syncthreads();
-  while (hi > 0) {
-    const int lo_bit = max(hi - 8, 0);
-    const uint32_t dmask = (1u << (hi - lo_bit)) - 1u;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    const uint32_t prefix = s_prefix;
-#pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-      const uint32_t k = key[j];
-      if (lo + 64 * j < T && (k & mask) == prefix) atomicAdd(&hist[(k >> lo_bit) & dmask], 1u);
-    }
-    __syncthreads();
-    if (tid < 64) wave_find_bin256<true>(hist, s_need, lo_bit, &s_prefix, &s_need);   // descending: B largest
-    mask |= dmask << lo_bit;
-    hi = lo_bit;
-    __syncthreads();
-  }
-  const uint32_t tau = s_prefix, need_eq = s_need;
+  uint32_t tau, need_eq;
+  block_radix_select<IPT, true>(key, valid, (uint32_t)B, rs, &tau, &need_eq);   // descending: the B largest
   // wave totals of (key > tau) and (key == tau)
   uint32_t c_gt = 0, c_eq = 0;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
-    const bool in = lo + 64 * j < T;
+    const bool in = (valid >> j) & 1u;
     c_gt += __popcll(__builtin_amdgcn_ballot_w64(in && key[j] > tau));
     c_eq += __popcll(__builtin_amdgcn_ballot_w64(in && key[j] == tau));
   }
@@ -122,16 +79,16 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
     weq[w] = c_eq;
   }
   __syncthreads();
-  uint32_t n_gt = 0, n_eq = 0;   // taken candidates at earlier positions: greater than the cut / equal to it
-  for (int i = 0; i < w; ++i) {
-    n_gt += wgt[i];
-    n_eq += weq[i];
-  }
+  // taken candidates at earlier positions (earlier waves): greater than the cut / equal to it
+  uint32_t n_gt = wave_incl_scan_u32(lane < w ? wgt[lane] : 0u);
+  uint32_t n_eq = wave_incl_scan_u32(lane < w ? weq[lane] : 0u);
+  n_gt = (uint32_t)__builtin_amdgcn_readlane((int)n_gt, 63);
+  n_eq = (uint32_t)__builtin_amdgcn_readlane((int)n_eq, 63);
   const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
     const int t = lo + 64 * j;
-    const bool in = t < T;
+    const bool in = (valid >> j) & 1u;
     const bool gt = in && key[j] > tau, eq = in && key[j] == tau;
     const unsigned long long m_gt = __builtin_amdgcn_ballot_w64(gt), m_eq = __builtin_amdgcn_ballot_w64(eq);
     const uint32_t gt_before = n_gt + __popcll(m_gt & below), eq_before = n_eq + __popcll(m_eq & below);
