@@ -58,6 +58,9 @@ typedef enum { QUOKA_F32 = 0, QUOKA_BF16 = 1 } quoka_dtype;
 enum {
   QUOKA_SCORE_DOT = 1,  /* dot products instead of cosines: neither the retained queries nor the keys are normalised */
   QUOKA_SCORE_MEAN = 2, /* mean instead of max over the retained-query axis                                          */
+  QUOKA_SCORE_QBAR_BF16 = 8, /* cheaper Qbar K^T (the direction the paper's conclusion names): Qbar is rounded to
+                                bfloat16 (nearest, ties to even) before the product; scores then differ from the
+                                exact ones by at most 2^-9 * sum_i |qbar_i| (times ||k|| with QUOKA_SCORE_DOT)     */
   QUOKA_SELECT_UNIFORM = 4 /* uniformly sampled queries (the query-sampling baseline of Sec. 4) instead of the lowest
                               cosines: positions floor(r * C / N_Q), r = 0..N_Q-1, the same for every head           */
 };
@@ -74,7 +77,7 @@ typedef struct quoka_shape {
   int32_t n_retain;     /* N_Q; N' = min(N_Q, C) queries are retained                         */
   int32_t max_budget;   /* B_max: extent of k_idx's last axis                                 */
   int32_t dtype;        /* quoka_dtype of Q, K, V, chunk K/V and O                            */
-  int32_t score_flags;  /* 0, or an OR of QUOKA_SCORE_DOT, QUOKA_SCORE_MEAN, QUOKA_SELECT_UNIFORM */
+  int32_t score_flags;  /* 0, or an OR of the QUOKA_SCORE_* / QUOKA_SELECT_* flags above                 */
   int64_t q_stride[3];  /* Q        [b, n_Q,  C,     d]: batch, head, token strides (elements) */
   int64_t kv_stride[3]; /* K, V     [b, n_KV, T_max, d] (K and V share strides)               */
   int64_t ck_stride[3]; /* chunk KV [b, n_KV, C,     d] (chunk K and V share strides)         */
@@ -104,7 +107,8 @@ quoka_status quoka_select_queries(const quoka_shape* shape, const void* q, int32
  *   scores   out  [b, n_KV, T_max] float32: scores[b,kv,t] = max_r <qbar[b,kv,r], K[b,kv,t]> /
  *                 max(||K[b,kv,t]||, 1e-8) for t < kv_lens[b]; entries t >= kv_lens[b] unspecified.
  *                 QUOKA_SCORE_DOT drops the division, QUOKA_SCORE_MEAN replaces max_r by the mean over r.
- * The product is accumulated in float32; for bf16 keys Qbar enters as an exact three-term bf16 split. */
+ * The product is accumulated in float32; for bf16 keys Qbar enters as an exact three-term bf16 split
+ * (one term, Qbar rounded to bf16, with QUOKA_SCORE_QBAR_BF16). */
 quoka_status quoka_score_keys(const quoka_shape* shape, const float* qbar, const void* k_cache,
                               const int32_t* kv_lens, float* scores, void* workspace, size_t workspace_bytes,
                               void* stream);

@@ -48,7 +48,9 @@ __device__ __forceinline__ float sumsq_bf16x8(const u32x4& r) {
   return s;
 }
 
-template <int D, int QB>
+// EXACT: Qbar enters as the three-term split (float32-exact products).  Otherwise it is rounded to bf16 once and
+// only that term is multiplied: a third of the matrix work, scores within 2^-9 * sum|qbar_i| of the exact ones.
+template <int D, int QB, bool EXACT>
 __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float* __restrict__ qbar,
                                                            const uint16_t* __restrict__ kc,
                                                            const int32_t* __restrict__ kv_lens,
@@ -112,12 +114,14 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const __bf16 h = (__bf16)x[e];
-        const float r1 = x[e] - (float)h;
-        const __bf16 m = (__bf16)r1;
-        const float r2 = r1 - (float)m;
         a_hi[ks][e] = h;
-        a_mid[ks][e] = m;
-        a_lo[ks][e] = (__bf16)r2;
+        if constexpr (EXACT) {
+          const float r1 = x[e] - (float)h;
+          const __bf16 m = (__bf16)r1;
+          const float r2 = r1 - (float)m;
+          a_mid[ks][e] = m;
+          a_lo[ks][e] = (__bf16)r2;
+        }
       }
     }
   }
@@ -180,10 +184,12 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
         bf16x8 kop[kPair];
 #pragma unroll
         for (int u = 0; u < kPair; ++u) kop[u] = *reinterpret_cast<const bf16x8*>(kp[u] + ks * 16);
+        if constexpr (EXACT) {
 #pragma unroll
-        for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo[ks], kop[u], c[u], 0, 0, 0);
+          for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo[ks], kop[u], c[u], 0, 0, 0);
 #pragma unroll
-        for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_mid[ks], kop[u], c[u], 0, 0, 0);
+          for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_mid[ks], kop[u], c[u], 0, 0, 0);
+        }
 #pragma unroll
         for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[ks], kop[u], c[u], 0, 0, 0);
       }
@@ -225,7 +231,9 @@ __global__ __launch_bounds__(kScThreads) void score_f32(Dims dm, const float* __
   const int T = min(kv_lens[b], dm.T_max);
   if ((int)(blockIdx.x * kScThreads) >= T) return;
   const float* qsrc = qbar + (size_t)(b * dm.n_kv + kv) * n_keep * D;
-  for (int i = threadIdx.x; i < n_keep * D; i += kScThreads) qs[i] = qsrc[i];
+  const bool round_q = (dm.flags & QUOKA_SCORE_QBAR_BF16) != 0;   // reduced-precision scorer: Qbar as bf16 values
+  for (int i = threadIdx.x; i < n_keep * D; i += kScThreads)
+    qs[i] = round_q ? bf16_bits_to_f32(f32_to_bf16_bits(qsrc[i])) : qsrc[i];
   __syncthreads();
   const int t = blockIdx.x * kScThreads + threadIdx.x;
   if (t >= T) return;
@@ -252,13 +260,13 @@ __global__ __launch_bounds__(kScThreads) void score_f32(Dims dm, const float* __
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int D, int QB>
+template <int D, int QB, bool EXACT>
 static hipError_t launch_bf16(const Dims& dm, const float* qbar, const void* kc, const int32_t* kv_lens, float* scores,
                               int n_keep, hipStream_t st) {
   using Cfg = ScoreCfg<D, QB>;
   static bool attr_done = false;  // benign race: the attribute call is idempotent
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_bf16<D, QB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_bf16<D, QB, EXACT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
     attr_done = true;
@@ -271,7 +279,7 @@ static hipError_t launch_bf16(const Dims& dm, const float* qbar, const void* kc,
   int tpw = (nt + wg_per_head - 1) / wg_per_head;
   tpw = tpw < 1 ? 1 : tpw;
   dim3 grid((nt + tpw - 1) / tpw, dm.n_kv, dm.b);
-  hipLaunchKernelGGL((score_bf16<D, QB>), grid, dim3(kScThreads), Cfg::kLdsBytes, st, dm, qbar,
+  hipLaunchKernelGGL((score_bf16<D, QB, EXACT>), grid, dim3(kScThreads), Cfg::kLdsBytes, st, dm, qbar,
                      static_cast<const uint16_t*>(kc), kv_lens, scores, n_keep, tpw);
   return hipGetLastError();
 }
@@ -280,9 +288,14 @@ template <int D>
 static hipError_t launch_bf16_d(const Dims& dm, const float* qbar, const void* kc, const int32_t* kv_lens,
                                 float* scores, int n_keep, hipStream_t st) {
   const int qblocks = (n_keep + 31) / 32;
-  if (qblocks <= 1) return launch_bf16<D, 1>(dm, qbar, kc, kv_lens, scores, n_keep, st);
-  if (qblocks == 2) return launch_bf16<D, 2>(dm, qbar, kc, kv_lens, scores, n_keep, st);
-  return launch_bf16<D, 4>(dm, qbar, kc, kv_lens, scores, n_keep, st);
+  if (dm.flags & QUOKA_SCORE_QBAR_BF16) {
+    if (qblocks <= 1) return launch_bf16<D, 1, false>(dm, qbar, kc, kv_lens, scores, n_keep, st);
+    if (qblocks == 2) return launch_bf16<D, 2, false>(dm, qbar, kc, kv_lens, scores, n_keep, st);
+    return launch_bf16<D, 4, false>(dm, qbar, kc, kv_lens, scores, n_keep, st);
+  }
+  if (qblocks <= 1) return launch_bf16<D, 1, true>(dm, qbar, kc, kv_lens, scores, n_keep, st);
+  if (qblocks == 2) return launch_bf16<D, 2, true>(dm, qbar, kc, kv_lens, scores, n_keep, st);
+  return launch_bf16<D, 4, true>(dm, qbar, kc, kv_lens, scores, n_keep, st);
 }
 
 hipError_t launch_score_keys(const Dims& dm, int dtype, const float* qbar, const void* k_cache, const int32_t* kv_lens,

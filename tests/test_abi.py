@@ -76,7 +76,7 @@ def test_workspace_query_and_status_strings(pk):
     (dict(chunk_len=0), 1),
     (dict(n_retain=0), 1),
     (dict(max_budget=2000), 1),                    # budget extent beyond the cache extent
-    (dict(score_flags=8), 1),
+    (dict(score_flags=16), 1),
     (dict(head_dim=96), 2),
     (dict(dtype=7), 2),
     (dict(n_retain=129), 2),

@@ -149,6 +149,49 @@ def test_ablation_scorers(case, flags):
         assert P.max_abs(got, lit) <= 4e-6 * scale * (4.0 if flags & 1 else 1.0)
 
 
+@pytest.mark.parametrize("flags", [8, 9, 10], ids=["qbar-bf16", "qbar-bf16+dot", "qbar-bf16+mean"])
+@pytest.mark.parametrize("case", ABLATION_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_reduced_precision_scorer(case, flags):
+    """Cheaper Qbar K^T (the paper's conclusion names it as future work): Qbar rounded to bfloat16 before the
+    product.  Q-bar itself is unchanged (float32); the scores must be the exact scores of the rounded Q-bar, and the
+    selected keys the top-B of those scores."""
+    pk = _pk()
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    budgets = [max(1, t // 6) for t in case["kv_lens"]]
+    w = gen.make_custom(batch=batch, budgets=budgets, seed=16, **case)
+    t = gen.to_torch(w, "cuda:0")
+    buf = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain,
+                          score_flags=flags)
+    similarity = "dot" if flags & 1 else "cosine"
+    reduce = "mean" if flags & 2 else "max"
+    buf.select_queries()
+    buf.scores.fill_(float("nan"))
+    buf.score_keys()
+    buf.topk_keys()
+    torch.cuda.synchronize()
+    q_idx, qbar, sc = gen.from_torch(buf.q_idx), gen.from_torch(buf.qbar), gen.from_torch(buf.scores)
+    k_idx, k_cnt = gen.from_torch(buf.k_idx), gen.from_torch(buf.k_cnt)
+    for b in range(w.batch):
+        T, B = w.kv_lens[b], w.budgets[b]
+        want_qbar = O.group_mean_queries(w.Q[b], q_idx[b], w.n_kv, similarity)
+        assert P.max_abs(qbar[b], want_qbar) <= P.TOL_QBAR * max(1.0, float(np.abs(want_qbar).max()))
+        want = O.key_scores_preagg(qbar[b].astype(np.float64), w.K[b][:, :T], similarity, reduce, qbar_bf16=True)
+        got = sc[b, :, :T]
+        assert not np.isnan(got).any()
+        scale = max(1.0, float(np.abs(want).max())) if T > 0 else 1.0
+        assert P.max_abs(got, want) <= P.TOL_SCORE * scale * (4.0 if flags & 1 else 1.0)
+        # not the exact scorer in disguise: the rounding is visible
+        exact = O.key_scores_preagg(qbar[b].astype(np.float64), w.K[b][:, :T], similarity, reduce)
+        # (with one head per group and dot products Q-bar is a bf16 query itself: nothing to round)
+        if T > 64 and not (flags & 1 and w.n_q == w.n_kv and w.dtype == "bf16"):
+            assert P.max_abs(want, exact) > 20 * P.TOL_SCORE * scale
+        for kv in range(w.n_kv):
+            n = int(k_cnt[b, kv])
+            assert n == min(B, T)
+            P.check_topk_set(k_idx[b, kv, :n], want[kv], B, what=f"b{b} kv{kv}")
+
+
 @pytest.mark.parametrize("flags", [4, 7], ids=["uniform", "uniform+dot+mean"])
 @pytest.mark.parametrize("case", ABLATION_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
 def test_uniform_query_sampling(case, flags):

@@ -177,3 +177,54 @@ def test_ablation_scorers_degenerate_cases():
     assert np.all(O.key_scores(Q, q_idx, K, 1, reduce="mean") <= O.key_scores(Q, q_idx, K, 1) + 1e-15)
     one = O.select_queries(Q[:, :1], 4)
     assert np.allclose(O.key_scores(Q[:, :1], one, K, 1, reduce="mean"), O.key_scores(Q[:, :1], one, K, 1), atol=1e-15)
+
+
+# ---- reduced-precision scorer (Q-bar in bfloat16; the cheaper product named as future work in Sec. 6) ------------
+def test_round_to_bf16_hand_values_and_ties_to_even():
+    one = 1.0
+    ulp = 2.0 ** -7                      # spacing of bfloat16 in [1, 2)
+    cases = [
+        (one, one),
+        (one + ulp, one + ulp),          # representable
+        (one + ulp / 2, one),            # tie -> even mantissa (1.0)
+        (one + 3 * ulp / 2, one + 2 * ulp),   # tie -> even mantissa (1 + 2 ulp)
+        (one + 0.49 * ulp, one),
+        (one + 0.51 * ulp, one + ulp),
+        (-(one + 0.51 * ulp), -(one + ulp)),
+        (2.0 - ulp / 4, 2.0),            # rounds up into the next binade
+        (3.0e-5, None), (0.0, 0.0),
+    ]
+    for x, want in cases:
+        got = float(O.round_to_bf16(np.array([x]))[0])
+        if want is None:
+            assert abs(got - x) <= abs(x) * 2.0 ** -9
+        else:
+            assert got == want, (x, got, want)
+
+
+def test_round_to_bf16_matches_the_library_conversion():
+    import torch
+    x = np.random.default_rng(3).standard_normal(4000).astype(np.float32) * np.float32(0.37)
+    x[:8] = [1.00390625, 1.01171875, -1.00390625, 0.333251953125, 65280.0, 1e-20, -3.0, 0.1]
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(O.round_to_bf16(x), want)
+
+
+def test_reduced_precision_scores_are_the_exact_scores_of_the_rounded_queries():
+    rng = np.random.default_rng(4)
+    qbar = rng.standard_normal((2, 5, 16)) * 0.2
+    K = rng.standard_normal((2, 30, 16))
+    got = O.key_scores_preagg(qbar, K, qbar_bf16=True)
+    # brute force with the library's rounding: cosine-style scores, max over queries
+    import torch
+    qr = torch.from_numpy(qbar.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    for kv in range(2):
+        for t in range(30):
+            k = K[kv, t] / np.linalg.norm(K[kv, t])
+            assert abs(got[kv, t] - max(float(qr[kv, r] @ k) for r in range(5))) < 1e-12
+    # bf16-exact queries: the option changes nothing
+    assert np.array_equal(O.key_scores_preagg(qr, K, qbar_bf16=True), O.key_scores_preagg(qr, K))
+    # and it stays within the rounding bound of the exact scores: |dq| <= 2^-9 |q| elementwise, |k-hat| = 1
+    exact = O.key_scores_preagg(qbar, K)
+    bound = 2.0 ** -9 * np.abs(qbar).sum(axis=2).max()
+    assert np.abs(got - exact).max() <= bound
