@@ -173,3 +173,42 @@ def test_config4_full_size():
 def test_config5_ragged_batch(n_retain, frac):
     w = gen.make_workload("c5", n_retain=n_retain, budget_frac=frac)
     _full_size_check(w, n_rows=24, dense_heads=[9], dense_rows=8)
+
+
+@pytest.mark.parametrize("case", [
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=200, n_retain=32, kv_lens=[1500, 700], budgets=[180, 90], batch=2),
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=3, n_retain=16, kv_lens=[2100], budgets=[260]),      # decode path
+    dict(dtype="bf16", n_q=4, n_kv=4, d=64, chunk=96, n_retain=16, kv_lens=[40000], budgets=[512]),     # multi-block top-k
+    dict(dtype="f32", n_q=4, n_kv=2, d=64, chunk=64, n_retain=16, kv_lens=[300], budgets=[40]),
+], ids=["prefill", "decode", "long", "f32"])
+def test_token_major_layout_gives_the_same_result(case):
+    """Caches are often stored token-major ([b, tokens, heads, d]).  The ABI takes strides, so such tensors are passed
+    as they are; every stage must produce exactly what it produces for the head-major copy of the same values."""
+    import paper_2602_08722_amd as pk
+    pk.load_library()
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    w = gen.make_custom(batch=batch, seed=23, **case)
+    t = gen.to_torch(w, "cuda:0")
+    tm = {k: v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for k, v in t.items() if k in ("q", "k", "v", "kc", "vc")}
+    assert tm["k"].stride() != t["k"].stride() or w.n_kv == 1
+    a = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain)
+    b = pk.ChunkBuffers(tm["q"], tm["k"], tm["v"], tm["kc"], tm["vc"], w.kv_lens, w.budgets, w.n_retain)
+    assert b.out.stride() == tm["q"].stride()          # the output takes the layout of Q
+    for buf in (a, b):
+        buf.out.zero_()
+        buf.chunk_attn()
+    torch.cuda.synchronize()
+    assert torch.equal(a.q_idx, b.q_idx)
+    assert torch.equal(a.qbar, b.qbar)
+    assert torch.equal(a.k_cnt, b.k_cnt)
+    for bi in range(w.batch):
+        n = int(a.k_cnt[bi, 0])
+        assert torch.equal(a.k_idx[bi, :, :n], b.k_idx[bi, :, :n])
+        T = w.kv_lens[bi]
+        assert torch.equal(a.scores[bi, :, :T], b.scores[bi, :, :T])
+    assert torch.equal(a.out, b.out)
+    a.dense_attn()
+    b.dense_attn()
+    torch.cuda.synchronize()
+    assert torch.equal(a.out, b.out)
