@@ -64,10 +64,7 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
   float* smax = ssq + 3 * kScTile;                                       // [3][QB][kScTile]
 
   const int kv = blockIdx.y, b = blockIdx.z;
-  const int T = min(kv_lens[b], dm.T_max);
   const int t_begin = blockIdx.x * tiles_per_wg * kScTile;
-  if (t_begin >= T) return;  // block-uniform
-  const int n_tiles = min(tiles_per_wg, (T - t_begin + kScTile - 1) / kScTile);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -86,12 +83,16 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
     const int t0 = t_begin + it * kScTile;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      int row = t0 + r0 + RPI * i;
-      row = row < T ? row : T - 1;  // tail rows re-read the last valid key; their scores are not stored
+      // rows are clamped to the cache extent, not to the sequence length: loads then do not wait for the length, and
+      // rows past it (allocated, arbitrary content) only produce scores that are never stored
+      const int row = min(t0 + r0 + RPI * i, dm.T_max - 1);
       R[i] = *reinterpret_cast<const u32x4*>(kbase + ((uint32_t)row * row_bytes + (uint32_t)cg * 16u));
     }
   };
-  issue(0, RA);   // the first K tiles are in flight while the query operands are prepared
+  issue(0, RA);   // the first K tile is in flight while the length arrives and the query operands are prepared
+  const int T = min(kv_lens[b], dm.T_max);
+  if (t_begin >= T) return;  // block-uniform
+  const int n_tiles = min(tiles_per_wg, (T - t_begin + kScTile - 1) / kScTile);
   if (n_tiles > 1) issue(1, RB);
 
   const bool dot_mode = (dm.flags & 1) != 0, mean_mode = (dm.flags & 2) != 0;   // ablation scorers
