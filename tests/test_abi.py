@@ -147,3 +147,19 @@ def test_product_path_never_touches_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f), encoding="utf-8").read()
                 assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+
+
+def test_flag_and_enum_values_match_the_header(pk):
+    """The Python constants are typed in by hand: check them against the declarations in include/quoka.h."""
+    text = open(os.path.join(ROOT, "include", "quoka.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    vals = {m.group(1): int(m.group(2)) for m in re.finditer(r"\b(QUOKA_[A-Z0-9_]+)\s*=\s*(\d+)", text)}
+    for name in ("QUOKA_F32", "QUOKA_BF16", "QUOKA_SCORE_DOT", "QUOKA_SCORE_MEAN", "QUOKA_SELECT_UNIFORM",
+                 "QUOKA_SCORE_QBAR_BF16"):
+        assert name in vals, name
+        assert getattr(pk, name) == vals[name], name
+    flags = [v for k, v in vals.items() if k.startswith(("QUOKA_SCORE_", "QUOKA_SELECT_"))]
+    assert sorted(flags) == [1, 2, 4, 8]           # distinct single bits
+    # every flag bit is accepted, the next bit is not
+    assert _ws_status(pk, _shape(pk, score_flags=15))[0] == 0
+    assert _ws_status(pk, _shape(pk, score_flags=16))[0] == 1
