@@ -42,6 +42,20 @@ constexpr int kSub = 64;           // keys a wave set consumes per step
 // SPLIT = true:  both sets own the same 4 row blocks; a staged tile has 128 keys, set s consumes keys 64*s..64*s+63,
 //                and the two partial results are merged through LDS at the end.  Used when 8 row blocks per block
 //                would leave compute units without a block.
+// Index of the sequence whose length has descending rank `rank` among lens[0], lens[stride], ... (nb <= 64 of them; ties
+// keep batch order).  Every wave works it out for itself: one load, nb lane reads, a ballot.
+__device__ __forceinline__ int seq_of_rank(const int32_t* __restrict__ lens, int stride, int nb, int rank) {
+  const int lane = threadIdx.x & 63;
+  const int mine = lane < nb ? lens[lane * stride] : -1;
+  int r = 0;
+  for (int j = 0; j < nb; ++j) {
+    const int other = __builtin_amdgcn_readlane(mine, j);
+    r += (other > mine) || (other == mine && j < lane);
+  }
+  const unsigned long long hit = __builtin_amdgcn_ballot_w64(lane < nb && r == rank);
+  return hit ? (int)__builtin_ctzll(hit) : rank;
+}
+
 template <int D, bool SPLIT>
 struct AttnCfg {
   static constexpr int KT = SPLIT ? 2 * kSub : kSub;  // keys per staged tile
@@ -66,7 +80,14 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
                 DB = Cfg::DB, HW = Cfg::HW;
   extern __shared__ __align__(16) unsigned char smem[];
 
-  const int kv = blockIdx.x, b = blockIdx.z;   // KV head fastest: one head's blocks share an XCD's L2
+  const int kv = blockIdx.x;   // KV head fastest: one head's blocks share an XCD's L2
+  const bool sparse = a.k_idx != nullptr;
+  // Blocks are dispatched in grid order and a block runs as long as its sequence's key list, so in a ragged batch the
+  // sequences are taken longest first (grid slice z works on the sequence of rank z by attended cache length);
+  // otherwise a long sequence that happens to come last starts when most of the chip has already drained.
+  int b = blockIdx.z;
+  if (dm.b > 1 && dm.b <= kWave)
+    b = seq_of_rank(sparse ? a.n_cache + kv : a.n_cache, sparse ? dm.n_kv : 1, dm.b, blockIdx.z);
   const int tid = threadIdx.x % kSetThreads, lane = tid & 63;                 // position inside the wave set
   // wave-uniform values are pinned to scalar registers so that everything derived from them (tile kind, base
   // pointers, branches) stays scalar too
@@ -92,7 +113,6 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
   const int c_end_blk = min((x_hi / g) * 32 + 32, C);   // chunk keys any wave of this block can see
   const int sub = SPLIT ? set * kSub : 0;               // first key of this set's share of a staged tile
 
-  const bool sparse = a.k_idx != nullptr;
   int n_cache;
   if (sparse) {
     n_cache = min(a.n_cache[b * dm.n_kv + kv], dm.B_max);
