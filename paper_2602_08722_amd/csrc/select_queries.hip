@@ -192,24 +192,16 @@ __global__ __launch_bounds__(kSelThreads) void sq_select(Dims dm, const float* _
   if (e < n_keep && part == 0) q_idx[(size_t)(b * dm.n_q + h) * n_keep + rank] = (int32_t)sel_idx[e];
 }
 
-__global__ void sq_identity(Dims dm, int32_t* __restrict__ q_idx, int n_keep) {
-  const int h = blockIdx.x, b = blockIdx.y;
-  for (int i = threadIdx.x; i < n_keep; i += blockDim.x) q_idx[(size_t)(b * dm.n_q + h) * n_keep + i] = i;
-}
-
-// Uniform query sampling (the query-sampling baseline of Sec. 4): an even stride over the chunk, no look at the data.
-__global__ void sq_uniform(Dims dm, int32_t* __restrict__ q_idx, int n_keep) {
-  const int h = blockIdx.x, b = blockIdx.y;
-  for (int r = threadIdx.x; r < n_keep; r += blockDim.x)
-    q_idx[(size_t)(b * dm.n_q + h) * n_keep + r] = (int32_t)(((int64_t)r * dm.C) / n_keep);
-}
-
 // ---------------------------------------------------------------------------------------------
 // One wave per (r, kv, b): lanes own D/64 consecutive elements each.  The group's rows are all requested before
 // any is used, so the kernel pays one index latency and one row latency, not g of each.
 constexpr int kGroupUnroll = 8;
-template <typename T, int D>
-__global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, const int32_t* __restrict__ q_idx,
+// RULE: where the retained positions come from.  kFromIndex: q_idx as written by the selection kernel.  The other two
+// are known in closed form, so this kernel writes q_idx itself and no separate launch is needed: kIdentity keeps every
+// query (C <= N_Q), kUniform takes the even stride floor(r * C / N') of the query-sampling baseline of Sec. 4.
+enum { kFromIndex = 0, kIdentity = 1, kUniform = 2 };
+template <typename T, int D, int RULE>
+__global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, int32_t* __restrict__ q_idx,
                                              float* __restrict__ qbar, int n_keep) {
   constexpr int EPL = D / 64;
   const int r = blockIdx.x, kv = blockIdx.y, b = blockIdx.z;
@@ -222,7 +214,13 @@ __global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, 
 #pragma unroll
     for (int jj = 0; jj < kGroupUnroll; ++jj) {
       const int j = min(j0 + jj, dm.g - 1);
-      tok[jj] = q_idx[(size_t)(b * dm.n_q + kv * dm.g + j) * n_keep + r];
+      int32_t* slot = q_idx + (size_t)(b * dm.n_q + kv * dm.g + j) * n_keep + r;
+      if constexpr (RULE == kFromIndex) {
+        tok[jj] = *slot;
+      } else {
+        tok[jj] = RULE == kIdentity ? r : (int)(((int64_t)r * dm.C) / n_keep);
+        if (lane == 0) *slot = tok[jj];
+      }
     }
     float v[kGroupUnroll][EPL];
 #pragma unroll
@@ -256,9 +254,12 @@ static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, fl
                                float* ws_cos, hipStream_t st) {
   const int n_keep = dm.n_ret < dm.C ? dm.n_ret : dm.C;
   const T* qp = static_cast<const T*>(q);
-  if (dm.C > dm.n_ret && (dm.flags & QUOKA_SELECT_UNIFORM)) {
-    hipLaunchKernelGGL(sq_uniform, dim3(dm.n_q, dm.b), dim3(64), 0, st, dm, q_idx, n_keep);
-  } else if (dm.C > dm.n_ret) {
+  const dim3 qgrid(n_keep, dm.n_kv, dm.b);
+  if (dm.C <= dm.n_ret) {
+    hipLaunchKernelGGL((sq_qbar<T, D, kIdentity>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
+  } else if (dm.flags & QUOKA_SELECT_UNIFORM) {
+    hipLaunchKernelGGL((sq_qbar<T, D, kUniform>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
+  } else {
     const int n_tiles = (dm.C + kSqTile - 1) / kSqTile;
     dim3 grid(n_tiles, dm.n_q, dm.b);
     hipLaunchKernelGGL((sq_partial_sums<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, n_tiles);
@@ -274,10 +275,8 @@ static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, fl
     } else {
       hipLaunchKernelGGL((sq_select<8>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
     }
-  } else {
-    hipLaunchKernelGGL(sq_identity, dim3(dm.n_q, dm.b), dim3(64), 0, st, dm, q_idx, n_keep);
+    hipLaunchKernelGGL((sq_qbar<T, D, kFromIndex>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
   }
-  hipLaunchKernelGGL((sq_qbar<T, D>), dim3(n_keep, dm.n_kv, dm.b), dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
   return hipGetLastError();
 }
 
