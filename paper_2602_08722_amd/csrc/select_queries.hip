@@ -122,7 +122,6 @@ __global__ __launch_bounds__(kSelThreads) void sq_select(Dims dm, const float* _
                                                         int32_t* __restrict__ q_idx, int n_keep) {
   constexpr int NW = kSelThreads / 64;
   __shared__ RadixSelectLds rs;
-  __shared__ uint32_t n_sel;
   __shared__ uint32_t wsum[NW + 1];
   __shared__ uint32_t sel_key[kMaxKeep];
   __shared__ uint32_t sel_idx[kMaxKeep];
@@ -139,31 +138,34 @@ __global__ __launch_bounds__(kSelThreads) void sq_select(Dims dm, const float* _
     key[j] = in ? okey(cv[lo + j]) : 0xFFFFFFFFu;
     valid |= (in ? 1u : 0u) << j;
   }
-  if (tid == 0) n_sel = 0;
   // tau: key of the n_keep-th smallest cosine; need_eq: how many elements equal to it are kept (lowest positions first)
   uint32_t tau, need_eq;
   block_radix_select<IPT, false>(key, valid, (uint32_t)n_keep, rs, &tau, &need_eq);
-  uint32_t c_eq = 0;
-#pragma unroll
-  for (int j = 0; j < IPT; ++j) c_eq += (lo + j < C) && (key[j] == tau);
-  uint32_t tot_eq;
-  uint32_t eq_rank = block_excl_scan<kSelThreads>(c_eq, wsum, &tot_eq);
+  // Retained queries go to LDS in position order.  One block scan carries both counts a thread needs (elements below
+  // the cut in the high half, elements equal to it in the low half; both fit 16 bits since C <= 8192).
+  uint32_t cnt = 0;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
-    if (lo + j < C) {
+    const bool in = (valid >> j) & 1u;
+    cnt += (in && key[j] == tau ? 1u : 0u) + (in && key[j] < tau ? 0x10000u : 0u);
+  }
+  uint32_t tot;
+  const uint32_t before = block_excl_scan<kSelThreads>(cnt, wsum, &tot);
+  uint32_t eq_rank = before & 0xFFFFu, lt_rank = before >> 16;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    if ((valid >> j) & 1u) {
       const uint32_t k = key[j];
-      bool take = k < tau;
-      if (k == tau) {
-        take = eq_rank < need_eq;
-        ++eq_rank;
-      }
-      if (take) {
-        const uint32_t slot = atomicAdd(&n_sel, 1u);   // slot order is irrelevant: ranks are computed below
+      const bool lt = k < tau, eq = k == tau;
+      if (lt || (eq && eq_rank < need_eq)) {   // equal cosines go to the lower positions
+        const uint32_t slot = lt_rank + min(eq_rank, need_eq);
         if (slot < (uint32_t)kMaxKeep) {
           sel_key[slot] = k;
           sel_idx[slot] = (uint32_t)(lo + j);
         }
       }
+      lt_rank += lt ? 1u : 0u;
+      eq_rank += eq ? 1u : 0u;
     }
   }
   __syncthreads();
