@@ -61,22 +61,21 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
     const bool in = lo + 64 * j < T;
-    key[j] = in ? okey(raw[j]) : 0u;
+    key[j] = in ? max(okey(raw[j]), 1u) : 0u;   // real keys are never 0, so the padding can neither exceed nor equal a cut key
     valid |= (in ? 1u : 0u) << j;
   }
   uint32_t tau, need_eq;
   block_radix_select<IPT, true>(key, valid, (uint32_t)B, rs, &tau, &need_eq);   // descending: the B largest
-  // wave totals of (key > tau) and (key == tau)
-  uint32_t c_gt = 0, c_eq = 0;
+  // wave totals of (key > tau) and (key == tau): per-lane counts (both in one register: at most 32 each), one scan
+  uint32_t cnt = 0;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
-    const bool in = (valid >> j) & 1u;
-    c_gt += __popcll(__builtin_amdgcn_ballot_w64(in && key[j] > tau));
-    c_eq += __popcll(__builtin_amdgcn_ballot_w64(in && key[j] == tau));
+    cnt += (key[j] > tau ? 0x10000u : 0u) + (key[j] == tau ? 1u : 0u);
   }
-  if (lane == 0) {
-    wgt[w] = c_gt;
-    weq[w] = c_eq;
+  cnt = wave_incl_scan_u32(cnt);
+  if (lane == 63) {
+    wgt[w] = cnt >> 16;
+    weq[w] = cnt & 0xFFFFu;
   }
   __syncthreads();
   // taken candidates at earlier positions (earlier waves): greater than the cut / equal to it
@@ -85,11 +84,14 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
   n_gt = (uint32_t)__builtin_amdgcn_readlane((int)n_gt, 63);
   n_eq = (uint32_t)__builtin_amdgcn_readlane((int)n_eq, 63);
   const unsigned long long below = (1ull << lane) - 1ull;
+  // (an opaque copy of the cut: otherwise the comparison masks of the counting loop above are kept alive for this
+  // loop, 2 x IPT scalar register pairs that spill)
+  uint32_t tau_e = tau;
+  asm volatile("" : "+v"(tau_e));
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
     const int t = lo + 64 * j;
-    const bool in = (valid >> j) & 1u;
-    const bool gt = in && key[j] > tau, eq = in && key[j] == tau;
+    const bool gt = key[j] > tau_e, eq = key[j] == tau_e;
     const unsigned long long m_gt = __builtin_amdgcn_ballot_w64(gt), m_eq = __builtin_amdgcn_ballot_w64(eq);
     const uint32_t gt_before = n_gt + __popcll(m_gt & below), eq_before = n_eq + __popcll(m_eq & below);
     if (gt || (eq && eq_before < need_eq)) {   // equal scores go to the lower positions
@@ -98,6 +100,7 @@ __global__ __launch_bounds__(kSmallThreads) void topk_small(Dims dm, const float
     }
     n_gt += __popcll(m_gt);
     n_eq += __popcll(m_eq);
+    __builtin_amdgcn_sched_barrier(0);   // keep one register's ballots live at a time (32 pairs would spill SGPRs)
   }
 }
 
