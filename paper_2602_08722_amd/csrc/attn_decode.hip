@@ -313,13 +313,9 @@ size_t attn_decode_ws_floats(const Dims& dm) {
 template <int D>
 static hipError_t launch_decode_d(const Dims& dm, const AttnArgs& a, float* part, hipStream_t st) {
   using Cfg = DecodeCfg<D>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_bf16<D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static std::atomic<uint64_t> lds_done{0};
+  const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_decode_bf16<D>), Cfg::kLdsBytes, lds_done);
+  if (e != hipSuccess) return e;
   const bool sparse = a.k_idx != nullptr;
   const int n_splits = decode_splits(dm, sparse);
   const long long max_keys = (long long)(sparse ? dm.B_max : dm.T_max) + dm.C;

@@ -396,13 +396,9 @@ template <int D, bool SPLIT>
 static hipError_t launch_ds(const Dims& dm, const AttnArgs& a, hipStream_t st) {
   using Cfg = AttnCfg<D, SPLIT>;
   constexpr size_t lds = Cfg::kLdsBytes;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16<D, SPLIT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static std::atomic<uint64_t> lds_done{0};
+  const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_bf16<D, SPLIT>), lds, lds_done);
+  if (e != hipSuccess) return e;
   const int nrb = dm.g * ((dm.C + 31) / 32);
   const int half = (nrb + 1) / 2;
   dim3 grid(dm.n_kv, (half + Cfg::HW - 1) / Cfg::HW, dm.b);

@@ -1,5 +1,6 @@
 // Internal launcher interface between the C-ABI layer (api.hip) and the kernel translation units.
 #pragma once
+#include <atomic>
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -7,6 +8,21 @@
 #include "common.hip.h"
 
 namespace quoka {
+
+// Kernels that use more than 64 KiB of dynamic LDS need the limit raised once per function and device.  `done` is a
+// per-function bit mask over device ordinals (a function-local static of the caller); the attribute call is
+// idempotent, so two threads racing through it are harmless, and the mask itself is atomic.
+inline hipError_t ensure_dynamic_lds(const void* func, size_t bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t{1} << dev) : 0;   // ordinals beyond 63: set it every time
+  if (bit != 0 && (done.load(std::memory_order_acquire) & bit) != 0) return hipSuccess;
+  e = hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return e;
+  done.fetch_or(bit, std::memory_order_release);
+  return hipSuccess;
+}
 
 // --- query sub-selection (select_queries.hip) -------------------------------------------------
 size_t select_queries_ws_floats(const Dims& dm);

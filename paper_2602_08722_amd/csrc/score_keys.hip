@@ -265,13 +265,10 @@ template <int D, int QB, bool EXACT>
 static hipError_t launch_bf16(const Dims& dm, const float* qbar, const void* kc, const int32_t* kv_lens, float* scores,
                               int n_keep, hipStream_t st) {
   using Cfg = ScoreCfg<D, QB>;
-  static bool attr_done = false;  // benign race: the attribute call is idempotent
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_bf16<D, QB, EXACT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static std::atomic<uint64_t> lds_done{0};
+  const hipError_t e =
+      ensure_dynamic_lds(reinterpret_cast<const void*>(&score_bf16<D, QB, EXACT>), Cfg::kLdsBytes, lds_done);
+  if (e != hipSuccess) return e;
   const int nt = (dm.T_max + kScTile - 1) / kScTile;
   const int heads = dm.b * dm.n_kv;
   // two blocks per compute unit are resident at once: aim for one round of 512 blocks, so the query operands
@@ -313,13 +310,9 @@ hipError_t launch_score_keys(const Dims& dm, int dtype, const float* qbar, const
     hipLaunchKernelGGL((score_f32<64>), grid, dim3(kScThreads), lds, st, dm, qbar, static_cast<const float*>(k_cache),
                        kv_lens, scores, n_keep);
   } else {
-    static bool attr_done = false;
-    if (!attr_done) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_f32<128>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 4);
-      if (e != hipSuccess) return e;
-      attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_done{0};
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&score_f32<128>), 128 * 128 * 4, lds_done);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((score_f32<128>), grid, dim3(kScThreads), lds, st, dm, qbar, static_cast<const float*>(k_cache),
                        kv_lens, scores, n_keep);
   }
