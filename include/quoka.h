@@ -131,7 +131,9 @@ quoka_status quoka_topk_keys(const quoka_shape* shape, const float* scores, cons
  *   k_idx [b, n_KV, B_max], k_cnt [b, n_KV] as written by quoka_topk_keys (any order is accepted;
  *   every index must be < T_max)
  *   lse   out, optional (may be NULL) [b, n_Q, C] float32: natural-log softmax normaliser per row.
- * bf16: QK^T and PV run on bf16 MFMA with float32 accumulation and float32 softmax state;
+ * bf16: QK^T and PV run on bf16 MFMA with float32 accumulation and float32 softmax state; the
+ *   factor log2(e)/sqrt(d) is multiplied into Q beforehand and P is the MFMA operand, so Q and P are
+ *   each rounded to bf16 once (outputs agree with exact arithmetic on the bf16 inputs to about 1e-2);
  * f32: all arithmetic in float32.                                                                  */
 quoka_status quoka_sparse_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
                                const int32_t* k_idx, const int32_t* k_cnt, const void* k_chunk,
