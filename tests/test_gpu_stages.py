@@ -333,10 +333,16 @@ ATTN_CASES = [
     dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=9, kv_lens=[300], budgets=[64]),         # 36 rows: prefill kernel
     dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=80, kv_lens=[150, 0, 64], budgets=[40, 9, 64], batch=3),
     dict(dtype="f32", n_q=4, n_kv=2, d=64, chunk=20, kv_lens=[90, 0], budgets=[30, 5], batch=2),
+    # ragged batches: the kernel takes the sequences longest first (up to 64 of them; beyond that in batch order)
+    dict(dtype="bf16", n_q=2, n_kv=1, d=64, chunk=40, kv_lens=[(37 * i) % 211 for i in range(64)],
+         budgets=[(37 * i) % 211 // 3 + 1 for i in range(64)], batch=64),
+    dict(dtype="bf16", n_q=2, n_kv=1, d=64, chunk=40, kv_lens=[(53 * i) % 173 for i in range(70)],
+         budgets=[(53 * i) % 173 // 2 + 1 for i in range(70)], batch=70),
 ]
 
 
-@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+@pytest.mark.parametrize("case", ATTN_CASES,
+                         ids=lambda c: "-".join(f"{k}{v}" if len(str(v)) < 40 else f"{k}[{len(v)} values]" for k, v in c.items()))
 def test_sparse_and_dense_attention(case):
     case = dict(case)
     batch = case.pop("batch", 1)
