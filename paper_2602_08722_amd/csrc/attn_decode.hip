@@ -72,6 +72,9 @@ __global__ __launch_bounds__(kDcThreads, 2) void attn_decode_bf16(Dims dm, AttnA
   const char* vchunk = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.v_chunk) + b * dm.cks[0] + kv * dm.cks[1]);
   const int32_t* kidx = sparse ? a.k_idx + (size_t)(b * dm.n_kv + kv) * dm.B_max : nullptr;
   const uint32_t cache_row_bytes = (uint32_t)dm.kvs[2] * 2u, chunk_row_bytes = (uint32_t)dm.cks[2] * 2u;
+  const uint64_t k_cache_u = reinterpret_cast<uint64_t>(kcache), v_cache_u = reinterpret_cast<uint64_t>(vcache);
+  const uint64_t k_chunk_delta = reinterpret_cast<uint64_t>(kchunk) - k_cache_u;   // modulo 2^64
+  const uint64_t v_chunk_delta = reinterpret_cast<uint64_t>(vchunk) - v_cache_u;
 
   // Q operand: row li -> (token li / g, head li % g); padding rows repeat row 0 and are never stored
   const int row = li < n_rows ? li : 0;
@@ -89,20 +92,23 @@ __global__ __launch_bounds__(kDcThreads, 2) void attn_decode_bf16(Dims dm, AttnA
   // all rows of a tile are requested together: indices first (one latency), then the rows (one latency)
   auto issue = [&](int t) __attribute__((always_inline)) {
     const int base = s_begin + t * kDcTile;
-    uint32_t off[NLD];
-    bool from_cache[NLD];
+    // addresses as integers (cache base, plus the distance to the chunk tensor for chunk rows): a per-lane choice
+    // between two pointers would be kept as a table in scratch memory
+    uint64_t ka[NLD], va[NLD];
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int n = min(base + r0 + RPI * i, s_end - 1);   // tail slots repeat a real row; they are masked below
-      from_cache[i] = n < n_cache;
-      int src = from_cache[i] ? n : n - n_cache;
-      if (from_cache[i] && sparse) src = kidx[n];
-      off[i] = (uint32_t)src * (from_cache[i] ? cache_row_bytes : chunk_row_bytes) + (uint32_t)cg * 16u;
+      const bool from_cache = n < n_cache;
+      int src = from_cache ? n : n - n_cache;
+      if (from_cache && sparse) src = kidx[n];
+      const uint64_t off = (uint64_t)((uint32_t)src * (from_cache ? cache_row_bytes : chunk_row_bytes) + (uint32_t)cg * 16u);
+      ka[i] = k_cache_u + (from_cache ? 0ull : k_chunk_delta) + off;
+      va[i] = v_cache_u + (from_cache ? 0ull : v_chunk_delta) + off;
     }
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      RK[i] = *reinterpret_cast<const u32x4*>((from_cache[i] ? kcache : kchunk) + off[i]);
-      RV[i] = *reinterpret_cast<const u32x4*>((from_cache[i] ? vcache : vchunk) + off[i]);
+      RK[i] = *reinterpret_cast<const u32x4*>(ka[i]);
+      RV[i] = *reinterpret_cast<const u32x4*>(va[i]);
     }
   };
   issue(0);
