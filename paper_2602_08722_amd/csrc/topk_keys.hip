@@ -141,12 +141,25 @@ __device__ __forceinline__ void find_bin(const uint32_t* __restrict__ hist, uint
   __syncthreads();
 }
 
-// Re-derive the cut after `npass` finished histogram passes.
-__device__ __forceinline__ Cut derive_cut(const uint32_t* __restrict__ hist, int npass, uint32_t B, uint32_t* sh) {
+// The cut after `npass` finished histogram passes.  Every pass adds one step (a bin and the rank left inside it).  A
+// kernel works out only the newest step, from the histogram the previous launch completed; the steps before it are
+// read back from `cuts` (two words per step), where block 0 of the launch that first derived them has left them
+// (`newest_stored`: a previous launch has already derived the newest step too).
+__device__ __forceinline__ Cut derive_cut(const uint32_t* __restrict__ hist, uint32_t* __restrict__ cuts, int npass,
+                                          bool newest_stored, uint32_t B, uint32_t* sh) {
   Cut c{0u, 0u, B};
   for (int p = 0; p < npass; ++p) {
     uint32_t bin, need;
-    find_bin(hist + p * kBins, radix_bins(p), c.need, sh, &bin, &need);
+    if (p + 1 < npass || newest_stored) {
+      bin = cuts[2 * p];
+      need = cuts[2 * p + 1];
+    } else {
+      find_bin(hist + p * kBins, radix_bins(p), c.need, sh, &bin, &need);
+      if (blockIdx.x == 0 && threadIdx.x == 0) {
+        cuts[2 * p] = bin;
+        cuts[2 * p + 1] = need;
+      }
+    }
     const int sft = radix_shift(p);
     c.prefix |= bin << sft;
     c.mask |= (radix_bins(p) - 1u) << sft;
@@ -159,10 +172,12 @@ __global__ void topk_zero(uint32_t* __restrict__ p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
+constexpr int kCutWords = 8;   // three (bin, rank) steps, padded
 struct LgCtx {
   int T, B;
   const float* sc;
   uint32_t* hist;
+  uint32_t* cuts;
   uint32_t* tcnt;
 };
 
@@ -174,9 +189,10 @@ __device__ __forceinline__ LgCtx lg_ctx(const Dims& dm, const float* scores, con
   c.B = max(0, min(min(budgets[b], c.T), dm.B_max));
   const size_t head = (size_t)(b * dm.n_kv + kv);
   c.sc = scores + head * dm.T_max;
-  const size_t per_head = 3 * (size_t)kBins + 2 * (size_t)n_tiles;
+  const size_t per_head = 3 * (size_t)kBins + kCutWords + 2 * (size_t)n_tiles;
   c.hist = ws + head * per_head;
-  c.tcnt = c.hist + 3 * kBins;
+  c.cuts = c.hist + 3 * kBins;
+  c.tcnt = c.cuts + kCutWords;
   return c;
 }
 
@@ -190,7 +206,7 @@ __global__ __launch_bounds__(kLgThreads) void topk_hist(Dims dm, const float* __
   const LgCtx c = lg_ctx(dm, scores, kv_lens, budgets, ws, n_tiles);
   const int t0 = blockIdx.x * kLgTile;
   if (c.B == 0 || c.B >= c.T || t0 >= c.T) return;   // block-uniform
-  const Cut cut = derive_cut(c.hist, PASS, (uint32_t)c.B, sh);
+  const Cut cut = derive_cut(c.hist, c.cuts, PASS, false, (uint32_t)c.B, sh);
   for (int i = threadIdx.x; i < kBins; i += kLgThreads) lh[i] = 0;
   __syncthreads();
   const int sft = radix_shift(PASS);
@@ -228,43 +244,52 @@ __global__ __launch_bounds__(kLgThreads) void topk_finish(Dims dm, const float* 
       for (int i = t0 + threadIdx.x; i < t1; i += kLgThreads) out[i] = i;
     return;
   }
-  const Cut cut = derive_cut(c.hist, 3, (uint32_t)c.B, sh);
+  const Cut cut = derive_cut(c.hist, c.cuts, 3, EMIT, (uint32_t)c.B, sh);   // the count pass leaves the last step for the emit pass
   const uint32_t tau = cut.prefix, need_eq = cut.need;
   // thread t owns kLgTile / kLgThreads consecutive scores
   constexpr int IPT = kLgTile / kLgThreads;
   const int lo = t0 + threadIdx.x * IPT;
   uint32_t kreg[IPT];
-  uint32_t c_gt = 0, c_eq = 0;
+  uint32_t cnt = 0;   // keys above the cut in the high half, keys equal to it in the low half (at most 2048 per tile)
 #pragma unroll
   for (int i = 0; i < IPT; ++i) {
     const int t = lo + i;
     const uint32_t k = t < t1 ? okey(c.sc[t]) : 0u;   // 0 is below every real key image except okey(-NaN); never > tau
     kreg[i] = k;
-    c_gt += (t < t1) && (k > tau);
-    c_eq += (t < t1) && (k == tau);
+    cnt += ((t < t1) && (k > tau) ? 0x10000u : 0u) + ((t < t1) && (k == tau) ? 1u : 0u);
   }
-  uint32_t tot_gt, tot_eq;
-  uint32_t p_gt = block_excl_scan<kLgThreads>(c_gt, sh, &tot_gt);
-  uint32_t p_eq = block_excl_scan<kLgThreads>(c_eq, sh, &tot_eq);
+  uint32_t tot;
+  const uint32_t before = block_excl_scan<kLgThreads>(cnt, sh, &tot);
   if (!EMIT) {
     if (threadIdx.x == 0) {
-      c.tcnt[2 * blockIdx.x] = tot_gt;
-      c.tcnt[2 * blockIdx.x + 1] = tot_eq;
+      c.tcnt[2 * blockIdx.x] = tot >> 16;
+      c.tcnt[2 * blockIdx.x + 1] = tot & 0xFFFFu;
     }
     return;
   }
-  // counts of all earlier tiles (fixed order; at most a few hundred tiles)
+  const uint32_t p_gt = before >> 16;
+  uint32_t p_eq = before & 0xFFFFu;
+  // counts of all earlier tiles (fixed order; at most a few hundred tiles): per-thread partial sums, one wave scan
+  // each, the four wave totals through LDS
   uint32_t e_gt = 0, e_eq = 0;
   for (int i = threadIdx.x; i < (int)blockIdx.x; i += kLgThreads) {
     e_gt += c.tcnt[2 * i];
     e_eq += c.tcnt[2 * i + 1];
   }
+  e_gt = wave_incl_scan_u32(e_gt);
+  e_eq = wave_incl_scan_u32(e_eq);
+  __syncthreads();   // sh is free again
+  if ((threadIdx.x & 63) == 63) {
+    sh[threadIdx.x >> 6] = e_gt;
+    sh[kLgThreads / 64 + (threadIdx.x >> 6)] = e_eq;
+  }
   __syncthreads();
-  uint32_t dummy;
-  (void)block_excl_scan<kLgThreads>(e_gt, sh, &tot_gt);
-  const uint32_t before_gt = tot_gt;
-  (void)block_excl_scan<kLgThreads>(e_eq, sh, &dummy);
-  const uint32_t before_eq = dummy;
+  uint32_t before_gt = 0, before_eq = 0;
+#pragma unroll
+  for (int i = 0; i < kLgThreads / 64; ++i) {
+    before_gt += sh[i];
+    before_eq += sh[kLgThreads / 64 + i];
+  }
   p_eq += before_eq;
   uint32_t pos = before_gt + p_gt + min(p_eq, need_eq);
 #pragma unroll
@@ -290,7 +315,7 @@ static inline int lg_tiles(const Dims& dm) { return (dm.T_max + kLgTile - 1) / k
 
 size_t topk_ws_words(const Dims& dm) {
   if (dm.T_max <= kSmallMax) return 0;
-  return (size_t)dm.b * dm.n_kv * (3 * (size_t)kBins + 2 * (size_t)lg_tiles(dm));
+  return (size_t)dm.b * dm.n_kv * (3 * (size_t)kBins + kCutWords + 2 * (size_t)lg_tiles(dm));
 }
 
 hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* kv_lens, const int32_t* budgets,
