@@ -7,8 +7,9 @@
 //   T_max <= kSmallMax : one 1024-thread block per head, keys held in registers, one launch.
 //   larger             : several blocks per head.  Three histogram passes (11 + 11 + 10 bits, global
 //                        integer atomics) find the cut key; a count pass and an emit pass produce
-//                        the ordered index list.  Each pass re-derives the cut prefix from the
-//                        finished histograms, so no kernel waits on another block.
+//                        the ordered index list.  Each launch derives the newest step of the cut
+//                        from the histogram the previous launch completed (and leaves it in the
+//                        workspace for the later ones), so no kernel waits on another block.
 #include "common.hip.h"
 #include "kernels.h"
 
