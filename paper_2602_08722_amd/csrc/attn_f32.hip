@@ -63,18 +63,19 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32(Dims dm, AttnArgs a) {
       dot += qs[w][d0 + 3] * kx.w;
     }
     const float s = valid ? dot * scale : -INFINITY;
-    const float m_new = fmaxf(m_run, group_max<64>(s));   // finite: key j0 is always visible
+    const float m_new = fmaxf(m_run, wave64_max(s));   // finite: key j0 is always visible
     const float alpha = expf(m_run - m_new);
     const float p = valid ? expf(s - m_new) : 0.f;
-    l_run = l_run * alpha + group_sum<64>(p);
+    l_run = l_run * alpha + wave64_sum(p);
     m_run = m_new;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] *= alpha;
     const int cnt = min(64, total - j0);
     for (int t = 0; t < cnt; ++t) {
-      const float pt = __shfl(p, t, 64);
-      const int ct = __shfl(is_chunk, t, 64);
-      const int rt = __shfl(row, t, 64);
+      // t is wave-uniform: lane reads through the scalar path instead of LDS shuffles
+      const float pt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p), t));
+      const int ct = __builtin_amdgcn_readlane(is_chunk, t);
+      const int rt = __builtin_amdgcn_readlane(row, t);
       const float* vp = ct ? vchunk + (size_t)rt * dm.cks[2] : vcache + (size_t)rt * dm.kvs[2];
 #pragma unroll
       for (int e = 0; e < EPL; ++e) acc[e] += pt * vp[lane + 64 * e];

@@ -69,12 +69,6 @@ __device__ __forceinline__ float group_sum(float x) {
   for (int o = W / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
   return x;
 }
-template <int W>
-__device__ __forceinline__ float group_max(float x) {
-#pragma unroll
-  for (int o = W / 2; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, kWave));
-  return x;
-}
 
 // Sum over each aligned group of 16 lanes (one DPP row) with four row rotations: plain VALU work, no LDS
 // crossbar traffic.  Every lane of the group gets the sum.
