@@ -255,12 +255,15 @@ class ChunkBuffers:
         quoka_sparse_attn(self.shape, self.q, self.k_cache, self.v_cache, self.k_idx, self.k_cnt, self.k_chunk,
                           self.v_chunk, self.out if out is None else out, self.lse if lse is None else lse,
                           self.workspace)
+        return self.out if out is None else out
 
     def dense_attn(self, out=None, lse=None):
         quoka_dense_attn(self.shape, self.q, self.k_cache, self.v_cache, self.kv_lens, self.k_chunk, self.v_chunk,
                          self.out if out is None else out, self.lse if lse is None else lse, self.workspace)
+        return self.out if out is None else out
 
     def chunk_attn(self):
         quoka_chunk_attn(self.shape, self.q, self.k_cache, self.v_cache, self.kv_lens, self.budgets, self.k_chunk,
                          self.v_chunk, self.q_idx, self.qbar, self.scores, self.k_idx, self.k_cnt, self.out, self.lse,
                          self.workspace)
+        return self.out
