@@ -212,3 +212,48 @@ def test_token_major_layout_gives_the_same_result(case):
     b.dense_attn()
     torch.cuda.synchronize()
     assert torch.equal(a.out, b.out)
+
+
+def _random_case(rnd, it):
+    """A small random problem: odd head counts, ragged sizes around the tile edges, empty and tiny caches."""
+    dtype = rnd.choice(["bf16", "bf16", "bf16", "f32"])
+    d = rnd.choice([64, 128])
+    n_kv = rnd.choice([1, 2, 3, 4])
+    g = rnd.choice([1, 2, 4, 8, 16]) if dtype == "bf16" else rnd.choice([1, 2])
+    batch = rnd.choice([1, 1, 2, 3])
+    chunk = rnd.choice([1, 2, 7, 16, 33, 64, 100, 129, 200, 257, 300])
+    n_retain = rnd.choice([1, 5, 16, 31, 32, 33, 64, 100, 128])
+    kv_lens = [rnd.choice([0, 1, 17, 63, 64, 65, 127, 128, 129, 500, 1000, 2049, 4097, 33000]) for _ in range(batch)]
+    budgets = [max(1, rnd.choice([1, t // 10 + 1, t // 3 + 1, t, t + 5])) for t in kv_lens]
+    if dtype == "f32":   # the float32 kernels are plain: keep their cases small
+        chunk = min(chunk, 100)
+        kv_lens = [min(t, 600) for t in kv_lens]
+        budgets = [min(b, 700) for b in budgets]
+    return dict(dtype=dtype, n_q=n_kv * g, n_kv=n_kv, d=d, chunk=chunk, n_retain=n_retain, kv_lens=kv_lens,
+                budgets=budgets, batch=batch, seed=2000 + it)
+
+
+@pytest.mark.parametrize("sweep", [0, 1, 2])
+def test_random_small_shapes(sweep):
+    """Seeded sweep over shapes nobody would pick by hand; every stage and both attention paths against the oracle."""
+    import random
+    rnd = random.Random(100 + sweep)
+    for it in range(10):
+        case = _random_case(rnd, 10 * sweep + it)
+        w = gen.make_custom(**case)
+        buf = _run(w)
+        out = gen.from_torch(buf.out)
+        for b in range(w.batch):
+            sel, _, _ = _check_selection(w, buf, b)
+            T = w.kv_lens[b]
+            idx = np.stack(sel) if len(sel[0]) > 0 else np.zeros((w.n_kv, 0), dtype=np.int64)
+            want = O.sparse_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], idx, w.Kc[b], w.Vc[b])
+            assert P.max_abs(out[b], want) <= P.TOL_OUT[w.dtype], f"{case} b{b}"
+        buf.out.fill_(float("nan"))
+        buf.dense_attn()
+        torch.cuda.synchronize()
+        out = gen.from_torch(buf.out)
+        for b in range(w.batch):
+            T = w.kv_lens[b]
+            want = O.dense_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], w.Kc[b], w.Vc[b])
+            assert P.max_abs(out[b], want) <= P.TOL_OUT[w.dtype], f"dense {case} b{b}"
