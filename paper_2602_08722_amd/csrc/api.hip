@@ -209,9 +209,25 @@ quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const voi
                               void* stream) {
   quoka_status st = quoka_select_queries(shape, q, q_idx, qbar, workspace, workspace_bytes, stream);
   if (st != QUOKA_OK) return st;
-  st = quoka_score_keys(shape, qbar, k_cache, kv_lens, scores, workspace, workspace_bytes, stream);
+  // Scoring and top-B as in quoka_score_keys / quoka_topk_keys (same checks), except that the scoring launch also
+  // clears the histograms of the multi-block top-k, which saves that stage a launch of its own.
+  Dims dm;
+  st = check_shape(shape, &dm);
   if (st != QUOKA_OK) return st;
-  st = quoka_topk_keys(shape, scores, kv_lens, budgets, k_idx, k_cnt, workspace, workspace_bytes, stream);
+  if (kv_lens == nullptr || budgets == nullptr || k_cnt == nullptr) return QUOKA_EINVAL;
+  if (dm.T_max > 0 && (k_cache == nullptr || scores == nullptr)) return QUOKA_EINVAL;
+  if (dm.B_max > 0 && k_idx == nullptr) return QUOKA_EINVAL;
+  if (!aligned16(k_cache)) return QUOKA_EINVAL;
+  const WsLayout l = layout(dm);   // (the workspace itself was checked by the call above)
+  uint32_t* topk_ws = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + l.topk_off);
+  const size_t topk_words = quoka::topk_ws_words(dm);
+  const bool fuse_clear = dm.T_max > 0 && topk_words > 0;
+  st = from_hip(quoka::launch_score_keys(dm, shape->dtype, qbar, k_cache, kv_lens, scores,
+                                         static_cast<hipStream_t>(stream), fuse_clear ? topk_ws : nullptr,
+                                         fuse_clear ? topk_words : 0));
+  if (st != QUOKA_OK) return st;
+  st = from_hip(quoka::launch_topk_keys(dm, scores, kv_lens, budgets, k_idx, k_cnt, topk_ws,
+                                        static_cast<hipStream_t>(stream), fuse_clear));
   if (st != QUOKA_OK) return st;
   return quoka_sparse_attn(shape, q, k_cache, v_cache, k_idx, k_cnt, k_chunk, v_chunk, out, lse, workspace,
                            workspace_bytes, stream);

@@ -30,13 +30,16 @@ hipError_t launch_select_queries(const Dims& dm, int dtype, const void* q, int32
                                  hipStream_t st);
 
 // --- key scoring (score_keys.hip) ---------------------------------------------------------------
+// `zero` / `zero_words`: optional side job for the fused call -- the scoring blocks clear that many 32-bit words (the
+// histograms the multi-block top-k that follows would otherwise clear with a launch of its own).
 hipError_t launch_score_keys(const Dims& dm, int dtype, const float* qbar, const void* k_cache, const int32_t* kv_lens,
-                             float* scores, hipStream_t st);
+                             float* scores, hipStream_t st, uint32_t* zero = nullptr, size_t zero_words = 0);
 
 // --- top-B key selection (topk_keys.hip) ----------------------------------------------------------
 size_t topk_ws_words(const Dims& dm);
+// `ws_is_zero`: the workspace words (topk_ws_words) have already been cleared on this stream.
 hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* kv_lens, const int32_t* budgets,
-                            int32_t* k_idx, int32_t* k_cnt, uint32_t* ws, hipStream_t st);
+                            int32_t* k_idx, int32_t* k_cnt, uint32_t* ws, hipStream_t st, bool ws_is_zero = false);
 
 // --- attention (attn_mfma.hip for bf16, attn_f32.hip for float32) ---------------------------------
 // Cache rows attended: sparse (k_idx != nullptr): k_idx[b,kv,0..k_cnt[b,kv]); dense: 0..kv_lens[b].

@@ -35,6 +35,14 @@ struct ScoreCfg {
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
+// Side job of the fused call: all blocks of the launch together clear `words` 32-bit words.
+__device__ __forceinline__ void clear_words(uint32_t* __restrict__ p, uint32_t words) {
+  if (p == nullptr) return;
+  const uint32_t nblk = gridDim.x * gridDim.y * gridDim.z;
+  const uint32_t blk = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  for (uint32_t i = blk * blockDim.x + threadIdx.x; i < words; i += nblk * blockDim.x) p[i] = 0u;
+}
+
 // sum of squares of the 8 bf16 values of a 16-byte chunk (products of bf16 pairs are exact in float32)
 __device__ __forceinline__ float sumsq_bf16x8(const u32x4& r) {
   // (the chunk is reinterpreted as a whole: casting single dwords of the vector to bf16 pairs is miscompiled)
@@ -54,8 +62,10 @@ template <int D, int QB, bool EXACT>
 __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float* __restrict__ qbar,
                                                            const uint16_t* __restrict__ kc,
                                                            const int32_t* __restrict__ kv_lens,
-                                                           float* __restrict__ scores, int n_keep, int tiles_per_wg) {
+                                                           float* __restrict__ scores, int n_keep, int tiles_per_wg,
+                                                           uint32_t* __restrict__ zero, uint32_t zero_words) {
   using Cfg = ScoreCfg<D, QB>;
+  clear_words(zero, zero_words);
   constexpr int KS = Cfg::KS, LD = Cfg::LD, CG = Cfg::CG, RPI = Cfg::RPI, NLD = Cfg::NLD, KPW = Cfg::KPW;
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* tile0p = reinterpret_cast<uint16_t*>(smem);
@@ -225,8 +235,9 @@ template <int D>
 __global__ __launch_bounds__(kScThreads) void score_f32(Dims dm, const float* __restrict__ qbar,
                                                        const float* __restrict__ kc,
                                                        const int32_t* __restrict__ kv_lens, float* __restrict__ scores,
-                                                       int n_keep) {
+                                                       int n_keep, uint32_t* __restrict__ zero, uint32_t zero_words) {
   extern __shared__ __align__(16) unsigned char smem[];
+  clear_words(zero, zero_words);
   float* qs = reinterpret_cast<float*>(smem);  // [n_keep][D]
   const int kv = blockIdx.y, b = blockIdx.z;
   const int T = min(kv_lens[b], dm.T_max);
@@ -263,7 +274,7 @@ __global__ __launch_bounds__(kScThreads) void score_f32(Dims dm, const float* __
 // ---------------------------------------------------------------------------------------------
 template <int D, int QB, bool EXACT>
 static hipError_t launch_bf16(const Dims& dm, const float* qbar, const void* kc, const int32_t* kv_lens, float* scores,
-                              int n_keep, hipStream_t st) {
+                              int n_keep, hipStream_t st, uint32_t* zero, uint32_t zero_words) {
   using Cfg = ScoreCfg<D, QB>;
   static std::atomic<uint64_t> lds_done{0};
   const hipError_t e =
@@ -278,43 +289,44 @@ static hipError_t launch_bf16(const Dims& dm, const float* qbar, const void* kc,
   tpw = tpw < 1 ? 1 : tpw;
   dim3 grid((nt + tpw - 1) / tpw, dm.n_kv, dm.b);
   hipLaunchKernelGGL((score_bf16<D, QB, EXACT>), grid, dim3(kScThreads), Cfg::kLdsBytes, st, dm, qbar,
-                     static_cast<const uint16_t*>(kc), kv_lens, scores, n_keep, tpw);
+                     static_cast<const uint16_t*>(kc), kv_lens, scores, n_keep, tpw, zero, zero_words);
   return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_bf16_d(const Dims& dm, const float* qbar, const void* kc, const int32_t* kv_lens,
-                                float* scores, int n_keep, hipStream_t st) {
+                                float* scores, int n_keep, hipStream_t st, uint32_t* zero, uint32_t zero_words) {
   const int qblocks = (n_keep + 31) / 32;
   if (dm.flags & QUOKA_SCORE_QBAR_BF16) {
-    if (qblocks <= 1) return launch_bf16<D, 1, false>(dm, qbar, kc, kv_lens, scores, n_keep, st);
-    if (qblocks == 2) return launch_bf16<D, 2, false>(dm, qbar, kc, kv_lens, scores, n_keep, st);
-    return launch_bf16<D, 4, false>(dm, qbar, kc, kv_lens, scores, n_keep, st);
+    if (qblocks <= 1) return launch_bf16<D, 1, false>(dm, qbar, kc, kv_lens, scores, n_keep, st, zero, zero_words);
+    if (qblocks == 2) return launch_bf16<D, 2, false>(dm, qbar, kc, kv_lens, scores, n_keep, st, zero, zero_words);
+    return launch_bf16<D, 4, false>(dm, qbar, kc, kv_lens, scores, n_keep, st, zero, zero_words);
   }
-  if (qblocks <= 1) return launch_bf16<D, 1, true>(dm, qbar, kc, kv_lens, scores, n_keep, st);
-  if (qblocks == 2) return launch_bf16<D, 2, true>(dm, qbar, kc, kv_lens, scores, n_keep, st);
-  return launch_bf16<D, 4, true>(dm, qbar, kc, kv_lens, scores, n_keep, st);
+  if (qblocks <= 1) return launch_bf16<D, 1, true>(dm, qbar, kc, kv_lens, scores, n_keep, st, zero, zero_words);
+  if (qblocks == 2) return launch_bf16<D, 2, true>(dm, qbar, kc, kv_lens, scores, n_keep, st, zero, zero_words);
+  return launch_bf16<D, 4, true>(dm, qbar, kc, kv_lens, scores, n_keep, st, zero, zero_words);
 }
 
 hipError_t launch_score_keys(const Dims& dm, int dtype, const float* qbar, const void* k_cache, const int32_t* kv_lens,
-                             float* scores, hipStream_t st) {
-  if (dm.T_max <= 0) return hipSuccess;
+                             float* scores, hipStream_t st, uint32_t* zero, size_t zero_words_sz) {
+  if (dm.T_max <= 0) return hipSuccess;   // (then the top-k that follows takes no workspace either)
+  const uint32_t zero_words = (uint32_t)zero_words_sz;
   const int n_keep = dm.n_ret < dm.C ? dm.n_ret : dm.C;
   if (dtype == QUOKA_BF16) {
-    return dm.d == 64 ? launch_bf16_d<64>(dm, qbar, k_cache, kv_lens, scores, n_keep, st)
-                      : launch_bf16_d<128>(dm, qbar, k_cache, kv_lens, scores, n_keep, st);
+    return dm.d == 64 ? launch_bf16_d<64>(dm, qbar, k_cache, kv_lens, scores, n_keep, st, zero, zero_words)
+                      : launch_bf16_d<128>(dm, qbar, k_cache, kv_lens, scores, n_keep, st, zero, zero_words);
   }
   dim3 grid((dm.T_max + kScThreads - 1) / kScThreads, dm.n_kv, dm.b);
   const size_t lds = (size_t)n_keep * dm.d * sizeof(float);
   if (dm.d == 64) {
     hipLaunchKernelGGL((score_f32<64>), grid, dim3(kScThreads), lds, st, dm, qbar, static_cast<const float*>(k_cache),
-                       kv_lens, scores, n_keep);
+                       kv_lens, scores, n_keep, zero, zero_words);
   } else {
     static std::atomic<uint64_t> lds_done{0};
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&score_f32<128>), 128 * 128 * 4, lds_done);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((score_f32<128>), grid, dim3(kScThreads), lds, st, dm, qbar, static_cast<const float*>(k_cache),
-                       kv_lens, scores, n_keep);
+                       kv_lens, scores, n_keep, zero, zero_words);
   }
   return hipGetLastError();
 }

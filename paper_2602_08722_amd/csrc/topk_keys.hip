@@ -320,7 +320,7 @@ size_t topk_ws_words(const Dims& dm) {
 }
 
 hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* kv_lens, const int32_t* budgets,
-                            int32_t* k_idx, int32_t* k_cnt, uint32_t* ws, hipStream_t st) {
+                            int32_t* k_idx, int32_t* k_cnt, uint32_t* ws, hipStream_t st, bool ws_is_zero) {
   if (dm.T_max <= kSmallMax) {
     const dim3 grid(dm.n_kv, dm.b), block(kSmallThreads);
     const int ipt = (dm.T_max + kSmallThreads - 1) / kSmallThreads;
@@ -341,7 +341,7 @@ hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* 
   }
   const int n_tiles = lg_tiles(dm);
   const size_t words = topk_ws_words(dm);
-  hipLaunchKernelGGL(topk_zero, dim3(256), dim3(256), 0, st, ws, words);
+  if (!ws_is_zero) hipLaunchKernelGGL(topk_zero, dim3(256), dim3(256), 0, st, ws, words);
   dim3 grid(n_tiles, dm.n_kv, dm.b);
   hipLaunchKernelGGL((topk_hist<0>), grid, dim3(kLgThreads), 0, st, dm, scores, kv_lens, budgets, ws, n_tiles);
   hipLaunchKernelGGL((topk_hist<1>), grid, dim3(kLgThreads), 0, st, dm, scores, kv_lens, budgets, ws, n_tiles);
