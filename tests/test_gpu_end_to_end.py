@@ -257,3 +257,37 @@ def test_random_small_shapes(sweep):
             T = w.kv_lens[b]
             want = O.dense_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], w.Kc[b], w.Vc[b])
             assert P.max_abs(out[b], want) <= P.TOL_OUT[w.dtype], f"dense {case} b{b}"
+
+
+@pytest.mark.parametrize("case", [
+    dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=64, n_retain=32, kv_lens=[40000, 35000], budgets=[4000, 100], batch=2),
+    dict(dtype="bf16", n_q=4, n_kv=2, d=128, chunk=96, n_retain=16, kv_lens=[3000], budgets=[300]),
+    dict(dtype="f32", n_q=2, n_kv=1, d=64, chunk=32, n_retain=8, kv_lens=[33000], budgets=[64]),
+], ids=["multi-block-topk", "single-block-topk", "f32-multi-block"])
+def test_fused_call_equals_the_stage_calls_on_a_dirty_workspace(case):
+    """quoka_chunk_attn shares work between stages (the scoring launch clears the top-k histograms).  With the
+    workspace filled with garbage before each run, it must give exactly what the four stage calls give."""
+    pk = _pk()
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    w = gen.make_custom(batch=batch, seed=51, **case)
+    t = gen.to_torch(w, "cuda:0")
+    res = []
+    for fused in (False, True, True):
+        buf = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain)
+        buf.workspace.fill_(0xA5)
+        buf.k_idx.fill_(-1)
+        buf.out.zero_()
+        if fused:
+            buf.chunk_attn()
+        else:
+            buf.select_queries()
+            buf.score_keys()
+            buf.topk_keys()
+            buf.sparse_attn()
+        torch.cuda.synchronize()
+        res.append((buf.q_idx.clone(), buf.qbar.clone(), buf.k_cnt.clone(), buf.k_idx.clone(), buf.out.clone()))
+    for other in res[1:]:
+        for a, b in zip(res[0], other):
+            assert torch.equal(a.view(torch.uint8) if a.dtype == torch.bfloat16 else a,
+                               b.view(torch.uint8) if b.dtype == torch.bfloat16 else b)
