@@ -46,6 +46,10 @@ def _parse():
                     help="instead of the chunk benchmark: whole-prompt chunked prefill (quoka_prefill_attn, one layer "
                          "of the c2 shape, chunk 1024, N_Q 64, budget 12 %% of the cache) at these prompt lengths, "
                          "sparse against dense; prints one JSON object")
+    ap.add_argument("--budget-sweep", action="store_true",
+                    help="instead of the chunk benchmark: the mixed-length batch c5 at N_Q in {32, 64, 128} x budget "
+                         "in {4, 12, 25} %% of each sequence's cache, each against the dense kernel on the same batch "
+                         "(the speed-up curve); prints one JSON object")
     ap.add_argument("--profile-stage", default=None,
                     choices=["select_queries", "score_keys", "topk_keys", "sparse_attn", "dense_attn", "copy"],
                     help="run only this stage --steps times (for rocprofv3 counter passes) and print a short JSON; "
@@ -149,6 +153,38 @@ def _prefill_sweep(args, torch, pk, dev):
                       "budget=12% of the cache", "data": "synthetic", "rows": rows}))
 
 
+def _budget_sweep(args, torch, gen, pk, dev):
+    """Speed-up over the dense kernel against the key budget and the number of retained queries, on the batch of eight
+    mixed-length sequences (workload c5).  The batch's data does not depend on the two knobs, so it is generated once."""
+    w = gen.make_workload("c5")
+    t = gen.to_torch(w, dev)
+    K, W = max(10, args.steps // 4), max(3, args.warmup // 4)
+
+    def timed(f):
+        for _ in range(W):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / K
+
+    dense = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain)
+    dense_us = timed(dense.dense_attn)
+    rows = []
+    for n_retain in (32, 64, 128):
+        for frac in (0.04, 0.12, 0.25):
+            budgets = [int(frac * x) for x in w.kv_lens]
+            bf = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, budgets, n_retain)
+            us = timed(bf.chunk_attn)
+            rows.append({"n_retain": n_retain, "budget_frac": frac, "sparse_us": us, "speedup_vs_dense": dense_us / us})
+            del bf
+    print(json.dumps({"mode": "budget_sweep", "workload": f"c5: b={w.batch} n_q={w.n_q} n_kv={w.n_kv} d={w.d} "
+                      f"T={w.kv_lens} C={w.chunk}", "data": "synthetic", "steps": K, "warmup": W,
+                      "dense_us": dense_us, "rows": rows}))
+
+
 def main():
     args = _parse()
     if args.gpus != 1:
@@ -165,6 +201,9 @@ def main():
     dev = "cuda:0"
     if args.prefill_sweep:
         _prefill_sweep(args, torch, pk, dev)
+        return
+    if args.budget_sweep:
+        _budget_sweep(args, torch, gen, pk, dev)
         return
     w = gen.make_workload(args.workload)
     t = gen.to_torch(w, dev)
@@ -241,8 +280,10 @@ def main():
         bf.sparse_attn()
         ev[i][4].record()
     torch.cuda.synchronize()
-    stage_us = {n: float(np.mean([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K)])) * 1e3
-                for j, n in enumerate(stage_names)}
+    stage_samples = {n: np.array([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K)]) * 1e3
+                     for j, n in enumerate(stage_names)}
+    stage_us = {n: float(np.mean(x)) for n, x in stage_samples.items()}
+    stage_pct = {n: [float(np.percentile(x, q)) for q in (10, 50, 90)] for n, x in stage_samples.items()}
     # average launch duration of the dominant kernel: K launches back to back between one pair of events
     # (a per-launch event pair would add its own few microseconds to a ~50 us kernel)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -296,6 +337,7 @@ def main():
         "dense_us_per_chunk": dense_ms * 1e3,
         "speedup_vs_dense": dense_ms / ms_per_step,
         "stages_us": stage_us,
+        "stages_us_p10_p50_p90": stage_pct,
         "dense_kernel_us": dense_kernel_us,
         "dense_mfma_frac": dense_tflops / MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else None,
         "score_keys_hbm_frac": score_gbs / HBM_PEAK_GBS,
