@@ -301,6 +301,19 @@ def main():
     torch.cuda.synchronize()
     dense_kernel_us = float(np.mean([a.elapsed_time(b) for a, b in evd])) * 1e3
 
+    # measured-achievable memory rate beside the vendor peak: a plain device copy of 1 GiB (read + write)
+    src = torch.ones(256 << 20, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+
     alg = _algorithmic(w)
     attn_us = attn_kernel_us
     sel_us = stage_us["score_keys"] + stage_us["topk_keys"]
@@ -342,6 +355,8 @@ def main():
         "dense_mfma_frac": dense_tflops / MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else None,
         "score_keys_hbm_frac": score_gbs / HBM_PEAK_GBS,
         "score_topk_hbm_frac": seltopk_gbs / HBM_PEAK_GBS,
+        "device_copy_gbs": copy_gbs,
+        "score_keys_frac_of_device_copy": score_gbs / copy_gbs,
         "roofline": roofline,
         "paper_context": "paper reports up to 5x attention speedup on NVIDIA A100 and ~7x on Intel Xeon (other hardware)",
     }
