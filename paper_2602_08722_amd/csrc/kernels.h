@@ -49,6 +49,7 @@ struct AttnArgs {
   const int32_t* n_cache;  // k_cnt [b,n_kv] (sparse) or kv_lens [b] (dense)
   void* out;
   float* lse;              // may be nullptr
+  int adjacent = 0;        // set by the launcher: row-block assignment of the bf16 kernel (paired or adjacent)
 };
 hipError_t launch_attn_bf16(const Dims& dm, const AttnArgs& a, hipStream_t st);
 // decode-sized chunks (g * C <= 32 query rows per KV head): split-KV kernel + merge, partials in `part`

@@ -169,6 +169,15 @@ def test_config4_full_size():
     _full_size_check(w, n_rows=48, dense_heads=[17], dense_rows=16)
 
 
+def test_launch_of_several_rounds_with_ragged_row_blocks():
+    """Enough row blocks for more than two blocks per compute unit: the attention kernel then groups neighbouring row
+    blocks and takes the longest causal ranges first.  188 row blocks per KV head do not fill the last block, one
+    sequence has an empty cache and one a budget equal to its cache."""
+    w = gen.make_custom(dtype="bf16", n_q=32, n_kv=8, d=64, chunk=1500, n_retain=64, kv_lens=[900, 0, 333],
+                        budgets=[100, 10, 333], batch=3, seed=88)
+    _full_size_check(w, n_rows=40, dense_heads=[3, 30], dense_rows=24)
+
+
 @pytest.mark.parametrize("n_retain,frac", [(32, 0.04), (64, 0.12), (128, 0.25)])
 def test_config5_ragged_batch(n_retain, frac):
     w = gen.make_workload("c5", n_retain=n_retain, budget_frac=frac)
