@@ -178,6 +178,13 @@ def test_launch_of_several_rounds_with_ragged_row_blocks():
     _full_size_check(w, n_rows=40, dense_heads=[3, 30], dense_rows=24)
 
 
+def test_largest_chunk_largest_group():
+    """The stated limits together: 8192 chunk tokens, 16 q-heads per KV head, 128 retained queries."""
+    w = gen.make_custom(dtype="bf16", n_q=16, n_kv=1, d=64, chunk=8192, n_retain=128, kv_lens=[5000], budgets=[600],
+                        seed=89)
+    _full_size_check(w, n_rows=40, dense_heads=[0, 15], dense_rows=16)
+
+
 @pytest.mark.parametrize("n_retain,frac", [(32, 0.04), (64, 0.12), (128, 0.25)])
 def test_config5_ragged_batch(n_retain, frac):
     w = gen.make_workload("c5", n_retain=n_retain, budget_frac=frac)
