@@ -399,3 +399,48 @@ def test_sparse_attention_accepts_unsorted_indices_and_strided_views():
     torch.cuda.synchronize()
     want = O.sparse_attn(w.Q[0], w.K[0], w.V[0], idx[0], w.Kc[0], w.Vc[0])
     assert P.max_abs(gen.from_torch(buf.out)[0], want) <= P.TOL_OUT["bf16"]
+
+
+def test_scoring_topk_and_attention_at_the_longest_cache():
+    """max_kv_len at its limit (2^24 - 1 tokens; one KV head of 64 dims keeps the head's rows below 4 GiB): 32-bit row
+    offsets, tile counts and histogram counts at their largest.  The cache is drawn on the device from a seeded
+    generator (2 GiB; the host generator would need minutes); scores are checked against the oracle on sampled
+    positions including both ends, the index set against the oracle's top-B of the very scores the kernel read, and
+    the attention output (values = keys) against the oracle run on the gathered rows."""
+    pk = _pk()
+    dev = "cuda:0"
+    T, d, C, B = (1 << 24) - 1, 64, 40, 4099
+    g = torch.Generator(device=dev).manual_seed(2024)
+    k = torch.randn((1, 1, T, d), device=dev, generator=g).to(torch.bfloat16)
+    q = torch.randn((1, 2, C, d), device=dev, generator=g).to(torch.bfloat16)
+    kc = torch.randn((1, 1, C, d), device=dev, generator=g).to(torch.bfloat16)
+    buf = pk.ChunkBuffers(q, k, k, kc, kc, [T], [B], n_retain=C)     # C <= N_Q: every query is kept
+    buf.scores.fill_(float("nan"))
+    buf.select_queries()
+    buf.score_keys()
+    buf.topk_keys()
+    torch.cuda.synchronize()
+    assert int(buf.k_cnt[0, 0]) == B
+    Q = q[0].float().cpu().numpy().astype(np.float64)
+    qbar = O.group_mean_queries(Q, O.select_queries(Q, C), 1)
+    rng = np.random.default_rng(7)
+    pos = np.unique(np.concatenate([np.arange(300), np.arange(T - 300, T), rng.integers(0, T, size=4000)]))
+    pos_t = torch.from_numpy(pos).to(dev)
+    Ks = k[0, :, pos_t].float().cpu().numpy().astype(np.float64)
+    want = O.key_scores_preagg(qbar, Ks)
+    got = buf.scores[0, :, pos_t].cpu().numpy()
+    assert not np.isnan(got).any()
+    assert P.max_abs(got, want) <= P.TOL_SCORE
+    sc = buf.scores[0, :, :T].cpu().numpy()
+    assert not np.isnan(sc).any()
+    want_idx = O.topk_keys(sc.astype(np.float64), B)
+    assert np.array_equal(buf.k_idx[0, :, :B].cpu().numpy(), want_idx)
+    # attention over rows gathered from all over the 2 GiB cache: the oracle gets the gathered rows as its whole cache
+    buf.out.fill_(float("nan"))
+    buf.sparse_attn()
+    torch.cuda.synchronize()
+    idx_t = torch.from_numpy(want_idx[0]).to(dev)
+    Kg = k[0, :, idx_t].float().cpu().numpy().astype(np.float64)
+    Kc = kc[0].float().cpu().numpy().astype(np.float64)
+    want_out = O.sparse_attn(Q, Kg, Kg, np.arange(B)[None], Kc, Kc)
+    assert P.max_abs(gen.from_torch(buf.out)[0], want_out) <= P.TOL_OUT["bf16"]
