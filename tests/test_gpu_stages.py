@@ -401,15 +401,16 @@ def test_sparse_attention_accepts_unsorted_indices_and_strided_views():
     assert P.max_abs(gen.from_torch(buf.out)[0], want) <= P.TOL_OUT["bf16"]
 
 
-def test_scoring_topk_and_attention_at_the_longest_cache():
-    """max_kv_len at its limit (2^24 - 1 tokens; one KV head of 64 dims keeps the head's rows below 4 GiB): 32-bit row
+@pytest.mark.parametrize("d", [64, 128])
+def test_scoring_topk_and_attention_at_the_longest_cache(d):
+    """max_kv_len at its limit (2^24 - 1 tokens; with 128 dims a head's rows end 256 bytes short of 4 GiB): 32-bit row
     offsets, tile counts and histogram counts at their largest.  The cache is drawn on the device from a seeded
-    generator (2 GiB; the host generator would need minutes); scores are checked against the oracle on sampled
+    generator (2 or 4 GiB; the host generator would need minutes); scores are checked against the oracle on sampled
     positions including both ends, the index set against the oracle's top-B of the very scores the kernel read, and
     the attention output (values = keys) against the oracle run on the gathered rows."""
     pk = _pk()
     dev = "cuda:0"
-    T, d, C, B = (1 << 24) - 1, 64, 40, 4099
+    T, C, B = (1 << 24) - 1, 40, 4099
     g = torch.Generator(device=dev).manual_seed(2024)
     k = torch.randn((1, 1, T, d), device=dev, generator=g).to(torch.bfloat16)
     q = torch.randn((1, 2, C, d), device=dev, generator=g).to(torch.bfloat16)
@@ -435,7 +436,7 @@ def test_scoring_topk_and_attention_at_the_longest_cache():
     assert not np.isnan(sc).any()
     want_idx = O.topk_keys(sc.astype(np.float64), B)
     assert np.array_equal(buf.k_idx[0, :, :B].cpu().numpy(), want_idx)
-    # attention over rows gathered from all over the 2 GiB cache: the oracle gets the gathered rows as its whole cache
+    # attention over rows gathered from all over the cache: the oracle gets the gathered rows as its whole cache
     buf.out.fill_(float("nan"))
     buf.sparse_attn()
     torch.cuda.synchronize()
