@@ -26,9 +26,10 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
 # `bench.py --profile-stage sparse_attn`, scaled by the same counters' reading for a 1 GiB device copy
-# (profiles/hbm_traffic_c2.txt, profiles/hbm_traffic_c4.txt: KiB read + KiB written).  None where it has not been
+# (profiles/hbm_traffic_c2.txt, hbm_traffic_c3_c5.txt, hbm_traffic_c4.txt: KiB read + KiB written).  None where it has not been
 # measured.
-MEASURED_TRAFFIC_BYTES = {"c2": (16449 + 8320) * 1024, "c4": (127638 + 33281) * 1024}
+MEASURED_TRAFFIC_BYTES = {"c2": (16449 + 8320) * 1024, "c3": (40596 + 16640) * 1024, "c4": (127638 + 33281) * 1024,
+                          "c5": (244391 + 33280) * 1024}
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
