@@ -144,35 +144,11 @@ def key_scores(Q: np.ndarray, q_idx: np.ndarray, K: np.ndarray, n_kv: int, simil
     return out
 
 
-def round_to_bf16(x: np.ndarray) -> np.ndarray:
-    """Nearest bfloat16 value (8 significant bits, ties to even) of every finite float32-representable entry,
-    returned as float64.  Used by the reduced-precision scorer below."""
-    f = np.asarray(x, dtype=np.float32)
-    out = np.empty(f.shape, dtype=np.float64)
-    flat_in, flat_out = f.reshape(-1), out.reshape(-1)
-    for i, v in enumerate(flat_in):
-        v = float(v)
-        if v == 0.0 or not np.isfinite(v):
-            flat_out[i] = v
-            continue
-        m, e = np.frexp(v)             # v = m * 2**e, 0.5 <= |m| < 1
-        scaled = m * 256.0             # 8 significant bits: integer part in [128, 256)
-        r = np.floor(scaled)
-        frac = scaled - r
-        if frac > 0.5 or (frac == 0.5 and int(r) % 2 == 1):
-            r += 1.0
-        flat_out[i] = float(np.ldexp(r / 256.0, int(e)))
-    return out
-
-
-def key_scores_preagg(qbar: np.ndarray, K: np.ndarray, similarity: str = "cosine", reduce: str = "max",
-                      qbar_bf16: bool = False) -> np.ndarray:
+def key_scores_preagg(qbar: np.ndarray, K: np.ndarray, similarity: str = "cosine", reduce: str = "max") -> np.ndarray:
     """S-hat [n_kv, T] from a given Q-bar: max_r <Q-bar_r, K_t / ||K_t||> (Alg. 1, S and S-hat steps);
     the ablation variants as in key_scores."""
     assert similarity in ("cosine", "dot") and reduce in ("max", "mean")
     qbar = np.asarray(qbar, dtype=np.float64)
-    if qbar_bf16:   # the cheaper product the paper names as future work (Sec. 6): Q-bar in bfloat16, keys as they are
-        qbar = round_to_bf16(qbar)
     Kn = np.asarray(K, dtype=np.float64)
     if similarity == "cosine":
         Kn = unit(Kn)

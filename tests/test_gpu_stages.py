@@ -7,6 +7,7 @@ import torch
 
 import gen
 from oracle import quoka_oracle as O
+from tests.bf16_round import round_to_bf16
 from tests import parity as P
 
 pytestmark = pytest.mark.gpu
@@ -176,7 +177,7 @@ def test_reduced_precision_scorer(case, flags):
         T, B = w.kv_lens[b], w.budgets[b]
         want_qbar = O.group_mean_queries(w.Q[b], q_idx[b], w.n_kv, similarity)
         assert P.max_abs(qbar[b], want_qbar) <= P.TOL_QBAR * max(1.0, float(np.abs(want_qbar).max()))
-        want = O.key_scores_preagg(qbar[b].astype(np.float64), w.K[b][:, :T], similarity, reduce, qbar_bf16=True)
+        want = O.key_scores_preagg(round_to_bf16(qbar[b]), w.K[b][:, :T], similarity, reduce)
         got = sc[b, :, :T]
         assert not np.isnan(got).any()
         scale = max(1.0, float(np.abs(want).max())) if T > 0 else 1.0

@@ -5,6 +5,7 @@ from scipy.spatial.distance import cdist
 
 import gen
 from oracle import quoka_oracle as O
+from tests.bf16_round import round_to_bf16
 
 
 def _rand(seed, *shape):
@@ -195,7 +196,7 @@ def test_round_to_bf16_hand_values_and_ties_to_even():
         (3.0e-5, None), (0.0, 0.0),
     ]
     for x, want in cases:
-        got = float(O.round_to_bf16(np.array([x]))[0])
+        got = float(round_to_bf16(np.array([x]))[0])
         if want is None:
             assert abs(got - x) <= abs(x) * 2.0 ** -9
         else:
@@ -207,14 +208,14 @@ def test_round_to_bf16_matches_the_library_conversion():
     x = np.random.default_rng(3).standard_normal(4000).astype(np.float32) * np.float32(0.37)
     x[:8] = [1.00390625, 1.01171875, -1.00390625, 0.333251953125, 65280.0, 1e-20, -3.0, 0.1]
     want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
-    assert np.array_equal(O.round_to_bf16(x), want)
+    assert np.array_equal(round_to_bf16(x), want)
 
 
 def test_reduced_precision_scores_are_the_exact_scores_of_the_rounded_queries():
     rng = np.random.default_rng(4)
     qbar = rng.standard_normal((2, 5, 16)) * 0.2
     K = rng.standard_normal((2, 30, 16))
-    got = O.key_scores_preagg(qbar, K, qbar_bf16=True)
+    got = O.key_scores_preagg(round_to_bf16(qbar), K)
     # brute force with the library's rounding: cosine-style scores, max over queries
     import torch
     qr = torch.from_numpy(qbar.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
@@ -223,7 +224,7 @@ def test_reduced_precision_scores_are_the_exact_scores_of_the_rounded_queries():
             k = K[kv, t] / np.linalg.norm(K[kv, t])
             assert abs(got[kv, t] - max(float(qr[kv, r] @ k) for r in range(5))) < 1e-12
     # bf16-exact queries: the option changes nothing
-    assert np.array_equal(O.key_scores_preagg(qr, K, qbar_bf16=True), O.key_scores_preagg(qr, K))
+    assert np.array_equal(round_to_bf16(qr), qr)
     # and it stays within the rounding bound of the exact scores: |dq| <= 2^-9 |q| elementwise, |k-hat| = 1
     exact = O.key_scores_preagg(qbar, K)
     bound = 2.0 ** -9 * np.abs(qbar).sum(axis=2).max()
