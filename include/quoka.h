@@ -129,7 +129,8 @@ quoka_status quoka_topk_keys(const quoka_shape* shape, const float* scores, cons
  *   j over cache rows k_idx[b,kv,0..k_cnt[b,kv]) and chunk rows c <= i.
  *   q, k_cache, v_cache, k_chunk, v_chunk  in (shape.dtype);  out [b, n_Q, C, d] (shape.dtype)
  *   k_idx [b, n_KV, B_max], k_cnt [b, n_KV] as written by quoka_topk_keys (any order is accepted;
- *   every index must be < T_max)
+ *   every index must be in [0, T_max): the kernels clamp an index outside that range to row T_max - 1,
+ *   so a malformed list gives a wrong result but never an access outside the cache)
  *   lse   out, optional (may be NULL) [b, n_Q, C] float32: natural-log softmax normaliser per row.
  * bf16: QK^T and PV run on bf16 MFMA with float32 accumulation and float32 softmax state; the
  *   factor log2(e)/sqrt(d) is multiplied into Q beforehand and P is the MFMA operand, so Q and P are
@@ -173,6 +174,15 @@ quoka_status quoka_prefill_attn(const quoka_shape* shape, int sparse, const void
                                 const int32_t* kv_lens_all, const int32_t* budgets_all, int32_t* q_idx, float* qbar,
                                 float* scores, int32_t* k_idx, int32_t* k_cnt, void* out, void* workspace,
                                 size_t workspace_bytes, void* stream);
+
+/* Measurement aids (no part of the method): kernels of known work for a benchmark to time beside the library's
+ * own kernels, so that rates can be quoted against what the GPU sustains as well as against its published peaks.
+ *   quoka_probe_mfma  `blocks` blocks of 4 waves, each wave issuing 4 * iters register-only
+ *                     v_mfma_f32_32x32x16_bf16 (32768 flop each); sink: device float, never written in practice.
+ *   quoka_probe_read  reads `bytes` (multiple of 16; src 16-byte aligned, device memory) once with coalesced
+ *                     16-byte loads and writes nothing.                                                         */
+quoka_status quoka_probe_mfma(int blocks, int iters, float* sink, void* stream);
+quoka_status quoka_probe_read(const void* src, size_t bytes, float* sink, void* stream);
 
 const char* quoka_status_string(quoka_status status);
 

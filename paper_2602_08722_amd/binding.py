@@ -21,9 +21,10 @@ _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = (
     "quoka_workspace_bytes", "quoka_select_queries", "quoka_score_keys", "quoka_topk_keys",
-    "quoka_sparse_attn", "quoka_dense_attn", "quoka_chunk_attn", "quoka_prefill_attn", "quoka_status_string",
-    "quoka_version",
+    "quoka_sparse_attn", "quoka_dense_attn", "quoka_chunk_attn", "quoka_prefill_attn",
+    "quoka_probe_mfma", "quoka_probe_read", "quoka_status_string", "quoka_version",
 )
+_STATUS_EXPORTS = EXPORTS[:-2]   # everything that returns a quoka_status
 
 
 class QuokaError(RuntimeError):
@@ -70,7 +71,9 @@ def load_library() -> ctypes.CDLL:
     lib.quoka_dense_attn.argtypes = [SH, P, P, P, I32P, P, P, P, F32P, P, SZ, P]
     lib.quoka_chunk_attn.argtypes = [SH, P, P, P, I32P, I32P, P, P, I32P, F32P, F32P, I32P, I32P, P, F32P, P, SZ, P]
     lib.quoka_prefill_attn.argtypes = [SH, ctypes.c_int, P, P, P, I32P, I32P, I32P, F32P, F32P, I32P, I32P, P, P, SZ, P]
-    for name in EXPORTS[:8]:
+    lib.quoka_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, F32P, P]
+    lib.quoka_probe_read.argtypes = [P, SZ, F32P, P]
+    for name in _STATUS_EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     lib.quoka_status_string.argtypes = [ctypes.c_int]
     lib.quoka_status_string.restype = ctypes.c_char_p
@@ -152,6 +155,14 @@ def quoka_topk_keys(shape, scores, kv_lens, budgets, k_idx, k_cnt, workspace, st
     _check("quoka_topk_keys", load_library().quoka_topk_keys(
         ctypes.byref(shape), _ptr(scores), _ptr(kv_lens), _ptr(budgets), _ptr(k_idx), _ptr(k_cnt), _ptr(workspace),
         workspace.numel(), _stream(stream)))
+
+
+def quoka_probe_mfma(blocks: int, iters: int, sink, stream=None) -> None:
+    _check("quoka_probe_mfma", load_library().quoka_probe_mfma(int(blocks), int(iters), _ptr(sink), _stream(stream)))
+
+
+def quoka_probe_read(src, nbytes: int, sink, stream=None) -> None:
+    _check("quoka_probe_read", load_library().quoka_probe_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)))
 
 
 def quoka_sparse_attn(shape, q, k_cache, v_cache, k_idx, k_cnt, k_chunk, v_chunk, out, lse, workspace,

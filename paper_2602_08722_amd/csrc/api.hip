@@ -267,6 +267,16 @@ quoka_status quoka_prefill_attn(const quoka_shape* shape, int sparse, const void
   return QUOKA_OK;
 }
 
+quoka_status quoka_probe_mfma(int blocks, int iters, float* sink, void* stream) {
+  if (blocks < 1 || blocks > 65535 || iters < 1 || sink == nullptr) return QUOKA_EINVAL;
+  return from_hip(quoka::launch_probe_mfma(blocks, iters, sink, static_cast<hipStream_t>(stream)));
+}
+
+quoka_status quoka_probe_read(const void* src, size_t bytes, float* sink, void* stream) {
+  if (src == nullptr || sink == nullptr || bytes == 0 || bytes % 16 != 0 || !aligned16(src)) return QUOKA_EINVAL;
+  return from_hip(quoka::launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
+}
+
 const char* quoka_status_string(quoka_status status) {
   switch (status) {
     case QUOKA_OK: return "ok";

@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kDcThreads, 2) void attn_decode_bf16(Dims dm, AttnA
       const int n = min(base + r0 + RPI * i, s_end - 1);   // tail slots repeat a real row; they are masked below
       const bool from_cache = n < n_cache;
       int src = from_cache ? n : n - n_cache;
-      if (from_cache && sparse) src = kidx[n];
+      if (from_cache && sparse) src = (int)min((uint32_t)kidx[n], (uint32_t)(dm.T_max - 1));   // a malformed list cannot leave the cache
       const uint64_t off = (uint64_t)((uint32_t)src * (from_cache ? cache_row_bytes : chunk_row_bytes) + (uint32_t)cg * 16u);
       ka[i] = k_cache_u + (from_cache ? 0ull : k_chunk_delta) + off;
       va[i] = v_cache_u + (from_cache ? 0ull : v_chunk_delta) + off;

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32(Dims dm, AttnArgs a) {
     int is_chunk, row;
     if (jj < n_cache) {
       is_chunk = 0;
-      row = sparse ? kidx[jj] : jj;
+      row = sparse ? (int)min((uint32_t)kidx[jj], (uint32_t)(dm.T_max - 1)) : jj;   // a malformed list cannot leave the cache
     } else {
       is_chunk = 1;
       row = jj - n_cache;

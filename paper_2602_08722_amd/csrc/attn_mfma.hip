@@ -162,6 +162,7 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
   }
 
   const int cg = tid % CG, r0 = tid / CG;
+  const uint32_t idx_max = (uint32_t)max(dm.T_max - 1, 0);
   uint32_t rows[NLD];   // source rows of the tile to be issued next
   u32x4 R[NLD];         // staging registers of the tile in flight
 
@@ -179,7 +180,8 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
       if (cache_ && sparse) {                                                                      \
         _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                                          \
           const uint32_t n_ = (uint32_t)min(base_ + r0 + RPI * i, last_); /* tail slots repeat a real row */ \
-          rows[i] = *reinterpret_cast<const uint32_t*>(kidx + n_ * 4u);                            \
+          /* clamped to the cache extent: a malformed list (negative or too large) cannot leave the tensor */ \
+          rows[i] = min(*reinterpret_cast<const uint32_t*>(kidx + n_ * 4u), idx_max);               \
         }                                                                                          \
       } else {                                                                                     \
         _Pragma("unroll") for (int i = 0; i < NLD; ++i)                                            \

@@ -58,4 +58,8 @@ size_t attn_decode_ws_floats(const Dims& dm);
 hipError_t launch_attn_decode_bf16(const Dims& dm, const AttnArgs& a, float* part, hipStream_t st);
 hipError_t launch_attn_f32(const Dims& dm, const AttnArgs& a, hipStream_t st);
 
+// --- measurement aids (probes.hip) ------------------------------------------------------------------
+hipError_t launch_probe_mfma(int blocks, int iters, float* sink, hipStream_t st);
+hipError_t launch_probe_read(const void* src, size_t bytes, float* sink, hipStream_t st);
+
 }  // namespace quoka

@@ -140,6 +140,8 @@ def _full_size_check(w, n_rows, dense_heads, dense_rows):
         want = O.sparse_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], sel, w.Kc[b], w.Vc[b], rows=rows)
         err = P.max_abs(out[b][:, rows], want)
         assert err <= P.TOL_OUT[w.dtype], f"sparse b{b}: {err}"
+    if not dense_heads:
+        return total_subs
     # dense baseline on a few heads / rows
     dense_out = torch.empty_like(buf.out)
     buf.dense_attn(out=dense_out)
@@ -185,10 +187,40 @@ def test_largest_chunk_largest_group():
     _full_size_check(w, n_rows=40, dense_heads=[0, 15], dense_rows=16)
 
 
-@pytest.mark.parametrize("n_retain,frac", [(32, 0.04), (64, 0.12), (128, 0.25)])
+@pytest.mark.parametrize("frac", [0.04, 0.12, 0.25])
+@pytest.mark.parametrize("n_retain", [32, 64, 128])
 def test_config5_ragged_batch(n_retain, frac):
+    """All nine (N_Q, budget) points of the mixed-length batch: the three N_Q values take three variants of the scoring
+    kernel and the budgets fall on both sides of the single-block / multi-block top-k boundary.  Selection stages are
+    checked in full, attention on sampled rows; the dense baseline (the same for all points) on the diagonal only."""
     w = gen.make_workload("c5", n_retain=n_retain, budget_frac=frac)
-    _full_size_check(w, n_rows=24, dense_heads=[9], dense_rows=8)
+    diag = (n_retain, frac) in ((32, 0.04), (64, 0.12), (128, 0.25))
+    _full_size_check(w, n_rows=24, dense_heads=[9] if diag else [], dense_rows=8)
+
+
+def test_config5_full_budget_is_the_dense_baseline():
+    """Budget 100 % on the mixed-length batch (the last point of the speed-up curve): every cache position is selected,
+    in order, so the sparse path runs the dense kernel's arithmetic on the same key order -- identical output bits --
+    and both agree with the oracle's dense attention."""
+    w = gen.make_workload("c5", n_retain=64, budget_frac=1.0)
+    assert w.budgets == w.kv_lens
+    buf = _run(w)
+    cnt = gen.from_torch(buf.k_cnt)
+    for b, T in enumerate(w.kv_lens):
+        assert cnt[b].tolist() == [T] * w.n_kv
+        assert torch.equal(buf.k_idx[b, :, :T], torch.arange(T, dtype=torch.int32, device="cuda:0").expand(w.n_kv, T))
+    sparse_out = buf.out.clone()
+    dense_out = torch.empty_like(buf.out)
+    buf.dense_attn(out=dense_out)
+    torch.cuda.synchronize()
+    assert torch.equal(sparse_out.view(torch.int16), dense_out.view(torch.int16))
+    out = gen.from_torch(sparse_out)
+    for b, T in enumerate(w.kv_lens):
+        rows = _sample_rows(w.chunk, 8, seed=300 + b)
+        heads = [b % w.n_q, (5 * b + 17) % w.n_q]
+        want = O.dense_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], w.Kc[b], w.Vc[b], rows=rows, heads=heads)
+        err = P.max_abs(out[b][heads][:, rows], want)
+        assert err <= P.TOL_OUT["bf16"], f"b{b}: {err}"
 
 
 @pytest.mark.parametrize("case", [
