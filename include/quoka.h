@@ -175,6 +175,19 @@ quoka_status quoka_prefill_attn(const quoka_shape* shape, int sparse, const void
                                 float* scores, int32_t* k_idx, int32_t* k_cnt, void* out, void* workspace,
                                 size_t workspace_bytes, void* stream);
 
+/* quoka_topk_keys for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus the workspace, same
+ * results bit for bit.  The histograms and per-tile counts of the multi-block path (max_kv_len > 32768) live in a
+ * 4 MiB array inside the library instead (one copy per GPU, held until the process ends); the call allocates
+ * nothing and frees nothing.  QUOKA_EWORKSPACE if the shape needs more than that array holds, i.e. if
+ *   batch * n_kv_heads * (6152 + 2 * ceil(max_kv_len / 2048)) * 4 bytes > QUOKA_NOALLOC_SCRATCH_BYTES
+ * (e.g. 64 KV-head slices of 131072 tokens need 1.6 MiB).  The call clears what it needs itself, so the array may
+ * hold anything on entry.  All calls on one GPU share that GPU's array: two such calls that overlap in time on the
+ * same GPU (different streams or threads) race; calls on one stream, or ordered by events, are safe.            */
+#define QUOKA_NOALLOC_SCRATCH_BYTES (4u << 20)
+quoka_status quoka_topk_keys_noalloc(const quoka_shape* shape, const float* scores, const int32_t* kv_lens,
+                                     const int32_t* budgets, int32_t* k_idx, int32_t* k_cnt, void* stream);
+
 /* Measurement aids (no part of the method): kernels of known work for a benchmark to time beside the library's
  * own kernels, so that rates can be quoted against what the GPU sustains as well as against its published peaks.
  *   quoka_probe_mfma  `blocks` blocks of 4 waves, each wave issuing 4 * iters register-only

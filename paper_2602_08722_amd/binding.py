@@ -21,7 +21,7 @@ _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = (
     "quoka_workspace_bytes", "quoka_select_queries", "quoka_score_keys", "quoka_topk_keys",
-    "quoka_sparse_attn", "quoka_dense_attn", "quoka_chunk_attn", "quoka_prefill_attn",
+    "quoka_sparse_attn", "quoka_dense_attn", "quoka_chunk_attn", "quoka_prefill_attn", "quoka_topk_keys_noalloc",
     "quoka_probe_mfma", "quoka_probe_read", "quoka_status_string", "quoka_version",
 )
 _STATUS_EXPORTS = EXPORTS[:-2]   # everything that returns a quoka_status
@@ -71,6 +71,7 @@ def load_library() -> ctypes.CDLL:
     lib.quoka_dense_attn.argtypes = [SH, P, P, P, I32P, P, P, P, F32P, P, SZ, P]
     lib.quoka_chunk_attn.argtypes = [SH, P, P, P, I32P, I32P, P, P, I32P, F32P, F32P, I32P, I32P, P, F32P, P, SZ, P]
     lib.quoka_prefill_attn.argtypes = [SH, ctypes.c_int, P, P, P, I32P, I32P, I32P, F32P, F32P, I32P, I32P, P, P, SZ, P]
+    lib.quoka_topk_keys_noalloc.argtypes = [SH, F32P, I32P, I32P, I32P, I32P, P]
     lib.quoka_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, F32P, P]
     lib.quoka_probe_read.argtypes = [P, SZ, F32P, P]
     for name in _STATUS_EXPORTS:
@@ -155,6 +156,11 @@ def quoka_topk_keys(shape, scores, kv_lens, budgets, k_idx, k_cnt, workspace, st
     _check("quoka_topk_keys", load_library().quoka_topk_keys(
         ctypes.byref(shape), _ptr(scores), _ptr(kv_lens), _ptr(budgets), _ptr(k_idx), _ptr(k_cnt), _ptr(workspace),
         workspace.numel(), _stream(stream)))
+
+
+def quoka_topk_keys_noalloc(shape, scores, kv_lens, budgets, k_idx, k_cnt, stream=None) -> None:
+    _check("quoka_topk_keys_noalloc", load_library().quoka_topk_keys_noalloc(
+        ctypes.byref(shape), _ptr(scores), _ptr(kv_lens), _ptr(budgets), _ptr(k_idx), _ptr(k_cnt), _stream(stream)))
 
 
 def quoka_probe_mfma(blocks: int, iters: int, sink, stream=None) -> None:

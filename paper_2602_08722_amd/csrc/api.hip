@@ -1,6 +1,9 @@
 // C-ABI layer of libquoka: argument validation, workspace carving, kernel dispatch.
-// Nothing here allocates, synchronises or keeps state.
+// Nothing here allocates or synchronises; the only state kept is the per-device address of the library-owned
+// scratch array of quoka_topk_keys_noalloc.
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 
 #include "kernels.h"
 #include "quoka.h"
@@ -91,6 +94,35 @@ bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0;
 quoka_status from_hip(hipError_t e) { return e == hipSuccess ? QUOKA_OK : QUOKA_EHIP; }
 
 }  // namespace
+
+// ---- entry point for callers that cannot allocate ------------------------------------------------------------
+// The multi-block top-k's histograms, cut steps and per-tile counts in an array the library owns.  `scratch` is the
+// host-side handle of the device array; its device address differs per GPU and is looked up once per device with
+// that device current.  Host code below only ever uses the looked-up pointer.
+namespace {
+constexpr size_t kScratchWords = QUOKA_NOALLOC_SCRATCH_BYTES / sizeof(uint32_t);
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) uint32_t scratch[kScratchWords];
+static std::atomic<uint32_t*> g_scratch_ptr[kMaxDevices];
+
+static hipError_t scratch_address(uint32_t** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  uint32_t* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));   // this device's copy of the array
+    if (e != hipSuccess) return e;
+    if (sym == nullptr) return hipErrorInvalidSymbol;
+    p = static_cast<uint32_t*>(sym);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // (two threads racing here store the same address)
+  }
+  *out = p;
+  return hipSuccess;
+}
 
 extern "C" {
 
@@ -265,6 +297,22 @@ quoka_status quoka_prefill_attn(const quoka_shape* shape, int sparse, const void
     if (st != QUOKA_OK) return st;
   }
   return QUOKA_OK;
+}
+
+quoka_status quoka_topk_keys_noalloc(const quoka_shape* shape, const float* scores, const int32_t* kv_lens,
+                                     const int32_t* budgets, int32_t* k_idx, int32_t* k_cnt, void* stream) {
+  Dims dm;
+  quoka_status st = check_shape(shape, &dm);
+  if (st != QUOKA_OK) return st;
+  if (kv_lens == nullptr || budgets == nullptr || k_cnt == nullptr) return QUOKA_EINVAL;
+  if (dm.T_max > 0 && scores == nullptr) return QUOKA_EINVAL;
+  if (dm.B_max > 0 && k_idx == nullptr) return QUOKA_EINVAL;
+  if (quoka::topk_ws_words(dm) > kScratchWords) return QUOKA_EWORKSPACE;
+  uint32_t* ws = nullptr;
+  if (scratch_address(&ws) != hipSuccess) return QUOKA_EHIP;
+  // the launcher clears the words it uses with a fill kernel of its own (no memset node, nothing allocated)
+  return from_hip(
+      quoka::launch_topk_keys(dm, scores, kv_lens, budgets, k_idx, k_cnt, ws, static_cast<hipStream_t>(stream)));
 }
 
 quoka_status quoka_probe_mfma(int blocks, int iters, float* sink, void* stream) {
