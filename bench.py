@@ -1,22 +1,25 @@
 #!/usr/bin/env python3
 """Benchmark of libquoka's per-chunk sparse attention path on one MI355X.
 
-One "step" = one pass of the whole hot path over one chunk: quoka_select_queries -> quoka_score_keys ->
-quoka_topk_keys -> quoka_sparse_attn, inputs resident in HBM.  The default workload is config c2
-(Llama-3-8B-shaped layer, 8192 cached tokens, chunk 1024, 64 retained queries, 12 % key budget).
+One "step" = one pass of the whole hot path over one chunk (quoka_chunk_attn: query sub-selection -> key scoring ->
+top-B selection -> sparse attention), inputs resident in HBM.  The headline workload is config c4, the largest
+single-GPU configuration (131072 cached tokens, chunk 4096, 128 retained queries, budget 8192); the same run also
+measures c2, c3 and c5 and reports them in the `configs` object.
 
-Prints ONE JSON line: whole-path microseconds per chunk (`value`), the in-repo dense HIP baseline and the
-speedup over it, per-stage times, a roofline object for the dominant kernel, and the CPU oracle timed on
-the host cores as a reference baseline.
+Prints ONE JSON line: whole-path microseconds per chunk (`value`), the in-repo dense HIP baseline and the speed-up
+over it, per-stage and per-kernel-group times, `roofline` for the dominant kernel (attention, bf16 MFMA),
+`roofline_score_topk` for the selection stages (HBM), both against the published peaks and against rates measured in
+the same run (a register-only MFMA loop, a streaming read, a device copy), and the CPU oracle timed on the host cores.
 
-K/V caches are rotated over enough distinct copies (> 512 MiB in total) that the 256 MB last-level cache
-cannot serve them: "HBM" numbers are HBM numbers.
+K/V caches are rotated over enough distinct copies (> 512 MiB in total) that the 256 MB last-level cache cannot serve
+them: "HBM" numbers are HBM numbers.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,16 +27,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
-# `bench.py --profile-stage sparse_attn`, scaled by the same counters' reading for a 1 GiB device copy
-# (profiles/hbm_traffic_c2.txt, hbm_traffic_c3_c5.txt, hbm_traffic_c4.txt: KiB read + KiB written).  None where it has not been
-# measured.
-MEASURED_TRAFFIC_BYTES = {"c2": (16449 + 8320) * 1024, "c3": (40596 + 16640) * 1024, "c4": (127638 + 33281) * 1024,
-                          "c5": (244391 + 33280) * 1024}
-
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_VALU_PEAK_TFLOPS = 157.3
+
+STAGES = ["select_queries", "score_keys", "topk_keys", "sparse_attn"]
 
 
 def _parse():
@@ -41,7 +39,9 @@ def _parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"],
+                    help="the headline workload (default c4, the largest single-GPU configuration)")
+    ap.add_argument("--no-configs", action="store_true", help="measure only the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate-mib", type=int, default=640, help="total MiB of distinct K/V copies to rotate over")
     ap.add_argument("--prefill-sweep", default=None, metavar="L1,L2,...",
@@ -53,7 +53,7 @@ def _parse():
                          "in {4, 12, 25} %% of each sequence's cache, each against the dense kernel on the same batch "
                          "(the speed-up curve); prints one JSON object")
     ap.add_argument("--profile-stage", default=None,
-                    choices=["select_queries", "score_keys", "topk_keys", "sparse_attn", "dense_attn", "copy"],
+                    choices=STAGES + ["dense_attn", "chunk_attn", "copy"],
                     help="run only this stage --steps times (for rocprofv3 counter passes) and print a short JSON; "
                          "'copy' runs a plain device copy of known size, used to calibrate the HBM byte counters")
     return ap.parse_args()
@@ -75,6 +75,21 @@ def _algorithmic(w):
         g["dense_flops"] += 4 * w.d * w.n_q * w.chunk * (T + (w.chunk + 1) / 2)
         g["sparse_bytes"] += 2 * w.n_q * w.chunk * w.d * es + 2 * w.n_kv * (Bp + w.chunk) * w.d * es
     return g
+
+
+def _profile_traffic(name, stage):
+    """HBM bytes per launch of `stage` at workload `name`, as measured by the rocprofv3 FETCH_SIZE / WRITE_SIZE passes
+    whose summary is profiles/hbm_traffic_<name>.txt (a line `TRAFFIC <stage> read_bytes=<n> write_bytes=<n>`).
+    Returns (bytes, file) or (None, None): the figure belongs to the profiled build, so the file is named with it."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, None
+    m = re.search(rf"^TRAFFIC {stage} read_bytes=(\d+) write_bytes=(\d+)", text, re.M)
+    if not m:
+        return None, None
+    return int(m.group(1)) + int(m.group(2)), os.path.relpath(path, ROOT)
 
 
 def _cpu_baseline(w):
@@ -120,8 +135,8 @@ def _cpu_baseline(w):
         sel_s, attn_s = sum(sel_t) / reps, sum(attn_t) / reps
     total = (sel_s + attn_s * (w.chunk / n_rows)) * (w.batch if w.batch > 1 else 1)
     return {"value": total * 1e6, "unit": "us/chunk", "cores": int(cores), "kind": "oracle",
-            "sample": (f"sequence 0 of {w.batch}: selection stages in full ({sel_s:.2f} s); attention on {n_rows} of "
-                       f"{w.chunk} query rows x all heads ({attn_s:.2f} s)"
+            "sample": (f"workload {w.name}, sequence 0 of {w.batch}: selection stages in full ({sel_s:.2f} s); attention "
+                       f"on {n_rows} of {w.chunk} query rows x all heads ({attn_s:.2f} s)"
                        + (", scaled to all rows" if n_rows < w.chunk else "")
                        + (f"; mean of {reps} repetitions" if reps > 1 else "")
                        + ("; scaled by the batch size" if w.batch > 1 else ""))}
@@ -187,6 +202,139 @@ def _budget_sweep(args, torch, gen, pk, dev):
                       "dense_us": dense_us, "rows": rows}))
 
 
+def _describe(w):
+    return (f"{w.name}: b={w.batch} n_q={w.n_q} n_kv={w.n_kv} d={w.d} T={w.kv_lens} C={w.chunk} "
+            f"N_Q={w.n_retain} B={w.budgets}")
+
+
+def _make_buffers(torch, gen, pk, w, dev, rotate_mib):
+    t = gen.to_torch(w, dev)
+    es = 2 if w.dtype == "bf16" else 4
+    copy_bytes = 2 * t["k"].numel() * es
+    n_copies = min(64, max(1, -(-rotate_mib * (1 << 20) // copy_bytes)))
+    bufs = []
+    for i in range(n_copies):
+        k = t["k"] if i == 0 else t["k"].clone()
+        v = t["v"] if i == 0 else t["v"].clone()
+        bufs.append(pk.ChunkBuffers(t["q"], k, v, t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain))
+    return bufs
+
+
+def _back_to_back(torch, calls, reps):
+    """Average time of one pass over `calls` when `reps` passes are enqueued back to back between ONE pair of events
+    on the launch stream: kernel time plus the launch gaps that a dependent chain really has, without the few
+    microseconds an event pair around every launch would add."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        for c in calls(i):
+            c()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def _measure(torch, np, bufs, w, K, W):
+    """All timings of one workload.  Whole path and dense baseline by the wall clock around K steps bracketed by
+    synchronisation; per-stage times from a second pass with an event pair per stage; kernel-group times (attention,
+    scoring, top-k, scoring + top-k) from back-to-back launches between one pair of events."""
+    n = len(bufs)
+
+    def step(i):
+        bufs[i % n].chunk_attn()
+
+    def dense_step(i):
+        bufs[i % n].dense_attn()
+
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(i)
+    torch.cuda.synchronize()
+    us_per_step = (time.perf_counter() - t0) * 1e6 / K
+
+    Kd = max(5, K // 5)   # the dense baseline is several times slower: fewer steps, same protocol
+    for i in range(max(2, W // 5)):
+        dense_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(Kd):
+        dense_step(i)
+    torch.cuda.synchronize()
+    dense_us = (time.perf_counter() - t0) * 1e6 / Kd
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(STAGES) + 1)] for _ in range(K)]
+    for i in range(K):
+        bf = bufs[i % n]
+        ev[i][0].record()
+        for j, name in enumerate(STAGES):
+            getattr(bf, name)()
+            ev[i][j + 1].record()
+    torch.cuda.synchronize()
+    samples = {name: np.array([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K)]) * 1e3
+               for j, name in enumerate(STAGES)}
+    stage_us = {name: float(np.mean(x)) for name, x in samples.items()}
+    stage_pct = {name: [float(np.percentile(x, q)) for q in (10, 50, 90)] for name, x in samples.items()}
+
+    kern = {
+        "sparse_attn": _back_to_back(torch, lambda i: [bufs[i % n].sparse_attn], K),
+        "dense_attn": _back_to_back(torch, lambda i: [bufs[i % n].dense_attn], Kd),
+        "score_keys": _back_to_back(torch, lambda i: [bufs[i % n].score_keys], K),
+        "topk_keys": _back_to_back(torch, lambda i: [bufs[i % n].topk_keys], K),
+        "score_topk": _back_to_back(torch, lambda i: [bufs[i % n].score_keys, bufs[i % n].topk_keys], K),
+        "select_queries": _back_to_back(torch, lambda i: [bufs[i % n].select_queries], K),
+    }
+    alg = _algorithmic(w)
+    res = {
+        "workload": _describe(w),
+        "us_per_chunk": us_per_step,
+        "dense_us_per_chunk": dense_us,
+        "speedup_vs_dense": dense_us / us_per_step,
+        "stages_us": stage_us,
+        "stages_us_p10_p50_p90": stage_pct,
+        "kernels_us": kern,
+        "kv_copies_rotated": n,
+    }
+    if w.dtype == "bf16":
+        res["sparse_attn_mfma_frac"] = alg["sparse_flops"] / (kern["sparse_attn"] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS
+        res["dense_attn_mfma_frac"] = alg["dense_flops"] / (kern["dense_attn"] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS
+    res["score_keys_hbm_frac"] = alg["score_bytes"] / (kern["score_keys"] * 1e-6) / 1e9 / HBM_PEAK_GBS
+    res["score_topk_hbm_frac"] = ((alg["score_bytes"] + alg["topk_bytes"]) / (kern["score_topk"] * 1e-6) / 1e9
+                                  / HBM_PEAK_GBS)
+    return res, alg
+
+
+def _probes(torch, pk, dev):
+    """Rates this GPU sustains in the same run, as second denominators beside the published peaks."""
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    src = torch.ones(256 << 20, dtype=torch.float32, device=dev)   # 1 GiB
+    dst = torch.empty_like(src)
+    blocks, iters = 1024, 20000
+    pk.quoka_probe_mfma(blocks, 200, sink)
+    pk.quoka_probe_read(src, src.numel() * 4, sink)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    ev[0].record()
+    pk.quoka_probe_mfma(blocks, iters, sink)
+    ev[1].record()
+    for _ in range(5):
+        pk.quoka_probe_read(src, src.numel() * 4, sink)
+    ev[2].record()
+    for _ in range(5):
+        dst.copy_(src)
+    ev[3].record()
+    torch.cuda.synchronize()
+    mfma = blocks * 4 * iters * 4 * 32768 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e12
+    read = 5 * src.numel() * 4 / (ev[1].elapsed_time(ev[2]) * 1e-3) / 1e9
+    copy = 5 * 2 * src.numel() * 4 / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9
+    return {"mfma_loop_tflops": mfma, "stream_read_gbs": read, "device_copy_gbs": copy,
+            "what": "register-only v_mfma_f32_32x32x16_bf16 loop (2 waves per SIMD); one coalesced read of 1 GiB; "
+                    "device copy of 1 GiB counted as read + write"}
+
+
 def main():
     args = _parse()
     if args.gpus != 1:
@@ -207,25 +355,8 @@ def main():
     if args.budget_sweep:
         _budget_sweep(args, torch, gen, pk, dev)
         return
-    w = gen.make_workload(args.workload)
-    t = gen.to_torch(w, dev)
-    es = 2 if w.dtype == "bf16" else 4
-    copy_bytes = 2 * t["k"].numel() * es
-    n_copies = max(1, -(-args.rotate_mib * (1 << 20) // copy_bytes))
-    n_copies = min(n_copies, 64)
-    bufs = []
-    for i in range(n_copies):
-        k = t["k"] if i == 0 else t["k"].clone()
-        v = t["v"] if i == 0 else t["v"].clone()
-        bufs.append(pk.ChunkBuffers(t["q"], k, v, t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain))
-
-    def step(i):
-        bufs[i % n_copies].chunk_attn()
-
-    def dense_step(i):
-        bufs[i % n_copies].dense_attn()
-
     K, W = args.steps, args.warmup
+    w = gen.make_workload(args.workload)
     if args.profile_stage is not None:
         if args.profile_stage == "copy":
             n = 256 << 20   # 1 GiB of float32 read + 1 GiB written per copy
@@ -237,131 +368,92 @@ def main():
             print(json.dumps({"profile_stage": "copy", "steps": K, "bytes_read_per_step": 4 * n,
                               "bytes_written_per_step": 4 * n}))
             return
-        for i in range(n_copies):   # every buffer set gets valid intermediates
-            step(i)
+        bufs = _make_buffers(torch, gen, pk, w, dev, args.rotate_mib)
+        for bf in bufs:   # every buffer set gets valid intermediates
+            bf.chunk_attn()
         torch.cuda.synchronize()
         for i in range(K):
-            getattr(bufs[i % n_copies], args.profile_stage)()
+            getattr(bufs[i % len(bufs)], args.profile_stage)()
         torch.cuda.synchronize()
         print(json.dumps({"profile_stage": args.profile_stage, "steps": K, "workload": w.name,
                           "algorithmic": _algorithmic(w)}))
         return
-    for i in range(W):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(K):
-        step(i)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / K
 
-    # dense baseline, same protocol (fewer steps: it is several times slower)
-    Kd = max(5, K // 5)
-    for i in range(max(2, W // 5)):
-        dense_step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(Kd):
-        dense_step(i)
-    torch.cuda.synchronize()
-    dense_ms = (time.perf_counter() - t0) * 1e3 / Kd
+    bufs = _make_buffers(torch, gen, pk, w, dev, args.rotate_mib)
+    head, alg = _measure(torch, np, bufs, w, K, W)
+    del bufs
+    torch.cuda.empty_cache()
+    probes = _probes(torch, pk, dev)
 
-    # second pass of the same K steps with HIP events around every stage (kept out of the headline timing,
-    # since the event records themselves cost a few microseconds per step)
-    stage_names = ["select_queries", "score_keys", "topk_keys", "sparse_attn"]
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
-    for i in range(K):
-        bf = bufs[i % n_copies]
-        ev[i][0].record()
-        bf.select_queries()
-        ev[i][1].record()
-        bf.score_keys()
-        ev[i][2].record()
-        bf.topk_keys()
-        ev[i][3].record()
-        bf.sparse_attn()
-        ev[i][4].record()
-    torch.cuda.synchronize()
-    stage_samples = {n: np.array([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K)]) * 1e3
-                     for j, n in enumerate(stage_names)}
-    stage_us = {n: float(np.mean(x)) for n, x in stage_samples.items()}
-    stage_pct = {n: [float(np.percentile(x, q)) for q in (10, 50, 90)] for n, x in stage_samples.items()}
-    # average launch duration of the dominant kernel: K launches back to back between one pair of events
-    # (a per-launch event pair would add its own few microseconds to a ~50 us kernel)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(K):
-        bufs[i % n_copies].sparse_attn()
-    e1.record()
-    torch.cuda.synchronize()
-    attn_kernel_us = e0.elapsed_time(e1) * 1e3 / K
-    evd = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(Kd)]
-    for i in range(Kd):
-        evd[i][0].record()
-        dense_step(i)
-        evd[i][1].record()
-    torch.cuda.synchronize()
-    dense_kernel_us = float(np.mean([a.elapsed_time(b) for a, b in evd])) * 1e3
-
-    # measured-achievable memory rate beside the vendor peak: a plain device copy of 1 GiB (read + write)
-    src = torch.ones(256 << 20, dtype=torch.float32, device=dev)
-    dst = torch.empty_like(src)
-    dst.copy_(src)
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for _ in range(5):
-        dst.copy_(src)
-    c1.record()
-    torch.cuda.synchronize()
-    copy_gbs = 5 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
-    del src, dst
-
-    alg = _algorithmic(w)
-    attn_us = attn_kernel_us
-    sel_us = stage_us["score_keys"] + stage_us["topk_keys"]
+    attn_us = head["kernels_us"]["sparse_attn"]
     attn_tflops = alg["sparse_flops"] / (attn_us * 1e-6) / 1e12
+    traffic, traffic_file = _profile_traffic(w.name, "sparse_attn")
     if w.dtype == "bf16":
         roofline = {"kernel": "attn_bf16 (quoka_sparse_attn)", "bound": "mfma", "achieved": attn_tflops,
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "algorithmic_bytes": alg["sparse_bytes"],
-                    "algorithmic_flops": alg["sparse_flops"], "kernel_us": attn_us}
+                    "traffic": traffic, "traffic_from_profile": traffic_file,
+                    "algorithmic_bytes": alg["sparse_bytes"], "algorithmic_flops": alg["sparse_flops"],
+                    "kernel_us": attn_us, "achievable_peak": probes["mfma_loop_tflops"],
+                    "frac_of_achievable": attn_tflops / probes["mfma_loop_tflops"]}
     else:
         roofline = {"kernel": "attn_f32 (quoka_sparse_attn)", "bound": "alu", "achieved": attn_tflops,
                     "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / FP32_VALU_PEAK_TFLOPS,
-                    "traffic": None}
-    score_gbs = alg["score_bytes"] / (stage_us["score_keys"] * 1e-6) / 1e9
-    seltopk_gbs = (alg["score_bytes"] + alg["topk_bytes"]) / (sel_us * 1e-6) / 1e9
-    dense_tflops = alg["dense_flops"] / (dense_kernel_us * 1e-6) / 1e12
+                    "traffic": None, "kernel_us": attn_us}
+    st_bytes = alg["score_bytes"] + alg["topk_bytes"]
+    st_us = head["kernels_us"]["score_topk"]
+    st_gbs = st_bytes / (st_us * 1e-6) / 1e9
+    sc_gbs = alg["score_bytes"] / (head["kernels_us"]["score_keys"] * 1e-6) / 1e9
+    st_traffic, st_file = _profile_traffic(w.name, "score_topk")
+    roofline_st = {"kernel": "score_keys + topk_keys (quoka_score_keys, quoka_topk_keys)", "bound": "hbm",
+                   "achieved": st_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": st_gbs / HBM_PEAK_GBS,
+                   "traffic": st_traffic, "traffic_from_profile": st_file, "algorithmic_bytes": st_bytes,
+                   "kernel_us": st_us, "achievable_peak": probes["stream_read_gbs"],
+                   "frac_of_achievable": st_gbs / probes["stream_read_gbs"],
+                   "score_keys_alone": {"achieved": sc_gbs, "frac": sc_gbs / HBM_PEAK_GBS,
+                                        "algorithmic_bytes": alg["score_bytes"],
+                                        "algorithmic_flops": alg["score_flops"],
+                                        "kernel_us": head["kernels_us"]["score_keys"]}}
 
     out = {
         "metric": "chunk_prefill_attention_us_per_chunk",
-        "value": ms_per_step * 1e3,
+        "value": head["us_per_chunk"],
         "unit": "us/chunk",
         "n_gpus": 1,
         "steps": K,
         "warmup": W,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": head["us_per_chunk"] * 1e-3,
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: b={w.batch} n_q={w.n_q} n_kv={w.n_kv} d={w.d} T={w.kv_lens} C={w.chunk} "
-                               f"N_Q={w.n_retain} B={w.budgets}",
-                   "kv_copies_rotated": n_copies},
-        "dense_us_per_chunk": dense_ms * 1e3,
-        "speedup_vs_dense": dense_ms / ms_per_step,
-        "stages_us": stage_us,
-        "stages_us_p10_p50_p90": stage_pct,
-        "dense_kernel_us": dense_kernel_us,
-        "dense_mfma_frac": dense_tflops / MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else None,
-        "score_keys_hbm_frac": score_gbs / HBM_PEAK_GBS,
-        "score_topk_hbm_frac": seltopk_gbs / HBM_PEAK_GBS,
-        "device_copy_gbs": copy_gbs,
-        "score_keys_frac_of_device_copy": score_gbs / copy_gbs,
+        "config": {"workload": head["workload"], "kv_copies_rotated": head["kv_copies_rotated"]},
+        "dense_us_per_chunk": head["dense_us_per_chunk"],
+        "speedup_vs_dense": head["speedup_vs_dense"],
+        "stages_us": head["stages_us"],
+        "stages_us_p10_p50_p90": head["stages_us_p10_p50_p90"],
+        "kernels_us": head["kernels_us"],
+        "dense_mfma_frac": head.get("dense_attn_mfma_frac"),
         "roofline": roofline,
+        "roofline_score_topk": roofline_st,
+        "probes": probes,
         "paper_context": "paper reports up to 5x attention speedup on NVIDIA A100 and ~7x on Intel Xeon (other hardware)",
     }
+    if not args.no_configs:
+        # the other bf16 configurations in the same run: fewer steps each, same protocol
+        Kc, Wc = max(10, K // 2), max(3, W // 2)
+        out["configs"] = {}
+        for name in ("c2", "c3", "c5"):
+            if name == w.name:
+                continue
+            wc = gen.make_workload(name)
+            bc = _make_buffers(torch, gen, pk, wc, dev, args.rotate_mib)
+            r, _ = _measure(torch, np, bc, wc, Kc, Wc)
+            r["steps"], r["warmup"] = Kc, Wc
+            r.pop("stages_us_p10_p50_p90")
+            out["configs"][name] = r
+            del bc, wc
+            torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(w)
     print(json.dumps(out))
