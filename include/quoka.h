@@ -123,6 +123,22 @@ quoka_status quoka_topk_keys(const quoka_shape* shape, const float* scores, cons
                              const int32_t* budgets, int32_t* k_idx, int32_t* k_cnt, void* workspace,
                              size_t workspace_bytes, void* stream);
 
+/* Key scoring and key selection as one stage (Alg. 1: S = Qbar K^T, S-hat = max, I = topk(S-hat, B_SA); the
+ * conclusion's "more efficient Qbar K^T").  Arguments as in quoka_score_keys and quoka_topk_keys.
+ *   k_idx, k_cnt  out  exactly what quoka_score_keys followed by quoka_topk_keys writes: the top-B of the exact
+ *                      scores, equal scores to the lower position, ascending.
+ *   scores        out  [b, n_KV, T_max] float32.  For bf16 caches longer than 32768 positions scored with the method's
+ *                      own rule (no QUOKA_SCORE_* flag) the stage scores every key with a single bf16 term of Qbar
+ *                      first and repeats the exact three-term product only for the keys whose provisional score lies
+ *                      within the proven error bound of the provisional cut; `scores` then holds the exact value
+ *                      (as quoka_score_keys computes it, bit for bit) for those keys -- at least every key within
+ *                      2^-11 of the cut -- and elsewhere the provisional value, which differs from the exact one by at
+ *                      most max_r ||qbar_r - bf16(qbar_r)||_2 + 4e-6 (<= 2^-9).  In every other case the stage is the
+ *                      two separate calls and `scores` is exact everywhere.                                          */
+quoka_status quoka_select_keys(const quoka_shape* shape, const float* qbar, const void* k_cache,
+                               const int32_t* kv_lens, const int32_t* budgets, float* scores, int32_t* k_idx,
+                               int32_t* k_cnt, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Chunk attention over the gathered cache rows and the chunk's own keys/values (Alg. 2 attention
  * step; Eq. 2-3).  For q-head h (KV head kv), chunk position i:
  *   O[b,h,i] = sum_j softmax_j(<Q[b,h,i], K_j> / sqrt(d)) V_j,
@@ -147,8 +163,9 @@ quoka_status quoka_dense_attn(const quoka_shape* shape, const void* q, const voi
                               const int32_t* kv_lens, const void* k_chunk, const void* v_chunk, void* out,
                               float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
-/* The four sparse stages back to back on one stream (Alg. 2, select-then-attend for one chunk).
- * Intermediates are returned to the caller: q_idx, qbar, scores, k_idx, k_cnt as above. */
+/* The sparse stages back to back on one stream (Alg. 2, select-then-attend for one chunk): quoka_select_queries,
+ * quoka_select_keys, quoka_sparse_attn.  Intermediates are returned to the caller: q_idx, qbar, k_idx, k_cnt as
+ * above, scores as quoka_select_keys leaves them. */
 quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
                               const int32_t* kv_lens, const int32_t* budgets, const void* k_chunk,
                               const void* v_chunk, int32_t* q_idx, float* qbar, float* scores, int32_t* k_idx,

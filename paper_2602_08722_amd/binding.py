@@ -20,7 +20,7 @@ _LIB_NAME = "libquoka.so"
 _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = (
-    "quoka_workspace_bytes", "quoka_select_queries", "quoka_score_keys", "quoka_topk_keys",
+    "quoka_workspace_bytes", "quoka_select_queries", "quoka_score_keys", "quoka_topk_keys", "quoka_select_keys",
     "quoka_sparse_attn", "quoka_dense_attn", "quoka_chunk_attn", "quoka_prefill_attn", "quoka_topk_keys_noalloc",
     "quoka_probe_mfma", "quoka_probe_read", "quoka_status_string", "quoka_version",
 )
@@ -67,6 +67,7 @@ def load_library() -> ctypes.CDLL:
     lib.quoka_select_queries.argtypes = [SH, P, I32P, F32P, P, SZ, P]
     lib.quoka_score_keys.argtypes = [SH, F32P, P, I32P, F32P, P, SZ, P]
     lib.quoka_topk_keys.argtypes = [SH, F32P, I32P, I32P, I32P, I32P, P, SZ, P]
+    lib.quoka_select_keys.argtypes = [SH, F32P, P, I32P, I32P, F32P, I32P, I32P, P, SZ, P]
     lib.quoka_sparse_attn.argtypes = [SH, P, P, P, I32P, I32P, P, P, P, F32P, P, SZ, P]
     lib.quoka_dense_attn.argtypes = [SH, P, P, P, I32P, P, P, P, F32P, P, SZ, P]
     lib.quoka_chunk_attn.argtypes = [SH, P, P, P, I32P, I32P, P, P, I32P, F32P, F32P, I32P, I32P, P, F32P, P, SZ, P]
@@ -156,6 +157,12 @@ def quoka_topk_keys(shape, scores, kv_lens, budgets, k_idx, k_cnt, workspace, st
     _check("quoka_topk_keys", load_library().quoka_topk_keys(
         ctypes.byref(shape), _ptr(scores), _ptr(kv_lens), _ptr(budgets), _ptr(k_idx), _ptr(k_cnt), _ptr(workspace),
         workspace.numel(), _stream(stream)))
+
+
+def quoka_select_keys(shape, qbar, k_cache, kv_lens, budgets, scores, k_idx, k_cnt, workspace, stream=None) -> None:
+    _check("quoka_select_keys", load_library().quoka_select_keys(
+        ctypes.byref(shape), _ptr(qbar), _ptr(k_cache), _ptr(kv_lens), _ptr(budgets), _ptr(scores), _ptr(k_idx),
+        _ptr(k_cnt), _ptr(workspace), workspace.numel(), _stream(stream)))
 
 
 def quoka_topk_keys_noalloc(shape, scores, kv_lens, budgets, k_idx, k_cnt, stream=None) -> None:
@@ -267,6 +274,10 @@ class ChunkBuffers:
 
     def topk_keys(self):
         quoka_topk_keys(self.shape, self.scores, self.kv_lens, self.budgets, self.k_idx, self.k_cnt, self.workspace)
+
+    def select_keys(self):
+        quoka_select_keys(self.shape, self.qbar, self.k_cache, self.kv_lens, self.budgets, self.scores, self.k_idx,
+                          self.k_cnt, self.workspace)
 
     def sparse_attn(self, out=None, lse=None):
         quoka_sparse_attn(self.shape, self.q, self.k_cache, self.v_cache, self.k_idx, self.k_cnt, self.k_chunk,

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libquoka.so")
 
-SOURCES = ["api.hip", "select_queries.hip", "score_keys.hip", "topk_keys.hip", "attn_mfma.hip", "attn_decode.hip", "attn_f32.hip",
+SOURCES = ["api.hip", "select_queries.hip", "score_keys.hip", "topk_keys.hip", "select_keys.hip", "attn_mfma.hip", "attn_decode.hip", "attn_f32.hip",
            "probes.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -23,6 +23,7 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct WsLayout {
   size_t select_off, select_bytes;
   size_t topk_off, topk_bytes;
+  size_t sel_off, sel_bytes;
   size_t decode_off, decode_bytes;
   size_t total;
 };
@@ -75,7 +76,9 @@ WsLayout layout(const Dims& dm) {
   l.select_bytes = round_up(quoka::select_queries_ws_floats(dm) * sizeof(float), kAlign);
   l.topk_off = l.select_off + l.select_bytes;
   l.topk_bytes = round_up(quoka::topk_ws_words(dm) * sizeof(uint32_t), kAlign);
-  l.decode_off = l.topk_off + l.topk_bytes;
+  l.sel_off = l.topk_off + l.topk_bytes;
+  l.sel_bytes = round_up(quoka::select_keys_ws_words(dm) * sizeof(uint32_t), kAlign);
+  l.decode_off = l.sel_off + l.sel_bytes;
   l.decode_bytes = dm.b > 0 ? round_up(quoka::attn_decode_ws_floats(dm) * sizeof(float), kAlign) : 0;
   l.total = l.decode_off + l.decode_bytes;
   if (l.total == 0) l.total = kAlign;
@@ -234,6 +237,41 @@ quoka_status quoka_dense_attn(const quoka_shape* shape, const void* q, const voi
                      workspace_bytes, stream);
 }
 
+// Scoring and top-B of one chunk on `stream`: the two-pass stage where it applies, else the two separate launches
+// (whose scoring launch clears the multi-block top-k's histograms).
+static quoka_status select_keys_common(const Dims& dm, int dtype, const float* qbar, const void* k_cache,
+                                       const int32_t* kv_lens, const int32_t* budgets, float* scores, int32_t* k_idx,
+                                       int32_t* k_cnt, void* workspace, const WsLayout& l, hipStream_t hs) {
+  if (dm.T_max > 0 && quoka::select_keys_two_pass_applies(dm, dtype)) {
+    uint32_t* sel_ws = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + l.sel_off);
+    return from_hip(quoka::launch_select_keys(dm, qbar, k_cache, kv_lens, budgets, scores, k_idx, k_cnt, sel_ws, hs));
+  }
+  uint32_t* topk_ws = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + l.topk_off);
+  const size_t topk_words = quoka::topk_ws_words(dm);
+  const bool fuse_clear = dm.T_max > 0 && topk_words > 0;
+  quoka_status st = from_hip(quoka::launch_score_keys(dm, dtype, qbar, k_cache, kv_lens, scores, hs,
+                                                      fuse_clear ? topk_ws : nullptr, fuse_clear ? topk_words : 0));
+  if (st != QUOKA_OK) return st;
+  return from_hip(quoka::launch_topk_keys(dm, scores, kv_lens, budgets, k_idx, k_cnt, topk_ws, hs, fuse_clear));
+}
+
+quoka_status quoka_select_keys(const quoka_shape* shape, const float* qbar, const void* k_cache,
+                               const int32_t* kv_lens, const int32_t* budgets, float* scores, int32_t* k_idx,
+                               int32_t* k_cnt, void* workspace, size_t workspace_bytes, void* stream) {
+  Dims dm;
+  quoka_status st = check_shape(shape, &dm);
+  if (st != QUOKA_OK) return st;
+  if (qbar == nullptr || kv_lens == nullptr || budgets == nullptr || k_cnt == nullptr) return QUOKA_EINVAL;
+  if (dm.T_max > 0 && (k_cache == nullptr || scores == nullptr)) return QUOKA_EINVAL;
+  if (dm.B_max > 0 && k_idx == nullptr) return QUOKA_EINVAL;
+  if (!aligned16(qbar) || !aligned16(k_cache)) return QUOKA_EINVAL;
+  const WsLayout l = layout(dm);
+  st = check_ws(l, workspace, workspace_bytes);
+  if (st != QUOKA_OK) return st;
+  return select_keys_common(dm, shape->dtype, qbar, k_cache, kv_lens, budgets, scores, k_idx, k_cnt, workspace, l,
+                            static_cast<hipStream_t>(stream));
+}
+
 quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
                               const int32_t* kv_lens, const int32_t* budgets, const void* k_chunk,
                               const void* v_chunk, int32_t* q_idx, float* qbar, float* scores, int32_t* k_idx,
@@ -241,25 +279,8 @@ quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const voi
                               void* stream) {
   quoka_status st = quoka_select_queries(shape, q, q_idx, qbar, workspace, workspace_bytes, stream);
   if (st != QUOKA_OK) return st;
-  // Scoring and top-B as in quoka_score_keys / quoka_topk_keys (same checks), except that the scoring launch also
-  // clears the histograms of the multi-block top-k, which saves that stage a launch of its own.
-  Dims dm;
-  st = check_shape(shape, &dm);
-  if (st != QUOKA_OK) return st;
-  if (kv_lens == nullptr || budgets == nullptr || k_cnt == nullptr) return QUOKA_EINVAL;
-  if (dm.T_max > 0 && (k_cache == nullptr || scores == nullptr)) return QUOKA_EINVAL;
-  if (dm.B_max > 0 && k_idx == nullptr) return QUOKA_EINVAL;
-  if (!aligned16(k_cache)) return QUOKA_EINVAL;
-  const WsLayout l = layout(dm);   // (the workspace itself was checked by the call above)
-  uint32_t* topk_ws = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + l.topk_off);
-  const size_t topk_words = quoka::topk_ws_words(dm);
-  const bool fuse_clear = dm.T_max > 0 && topk_words > 0;
-  st = from_hip(quoka::launch_score_keys(dm, shape->dtype, qbar, k_cache, kv_lens, scores,
-                                         static_cast<hipStream_t>(stream), fuse_clear ? topk_ws : nullptr,
-                                         fuse_clear ? topk_words : 0));
-  if (st != QUOKA_OK) return st;
-  st = from_hip(quoka::launch_topk_keys(dm, scores, kv_lens, budgets, k_idx, k_cnt, topk_ws,
-                                        static_cast<hipStream_t>(stream), fuse_clear));
+  st = quoka_select_keys(shape, qbar, k_cache, kv_lens, budgets, scores, k_idx, k_cnt, workspace, workspace_bytes,
+                         stream);
   if (st != QUOKA_OK) return st;
   return quoka_sparse_attn(shape, q, k_cache, v_cache, k_idx, k_cnt, k_chunk, v_chunk, out, lse, workspace,
                            workspace_bytes, stream);

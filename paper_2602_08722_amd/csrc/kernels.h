@@ -41,6 +41,17 @@ size_t topk_ws_words(const Dims& dm);
 hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* kv_lens, const int32_t* budgets,
                             int32_t* k_idx, int32_t* k_cnt, uint32_t* ws, hipStream_t st, bool ws_is_zero = false);
 
+// --- scoring + top-B as one stage for long caches (select_keys.hip) --------------------------------
+// Provisional one-term scores, exact re-scoring of the keys near the cut, ordered emission: the same index lists as
+// launch_score_keys followed by launch_topk_keys.  `ws_is_zero`: the first select_keys_zero_words words of the
+// workspace have already been cleared on this stream.
+bool select_keys_two_pass_applies(const Dims& dm, int dtype);
+size_t select_keys_ws_words(const Dims& dm);
+size_t select_keys_zero_words(const Dims& dm);
+hipError_t launch_select_keys(const Dims& dm, const float* qbar, const void* k_cache, const int32_t* kv_lens,
+                              const int32_t* budgets, float* scores, int32_t* k_idx, int32_t* k_cnt, uint32_t* ws,
+                              hipStream_t st, bool ws_is_zero = false);
+
 // --- attention (attn_mfma.hip for bf16, attn_f32.hip for float32) ---------------------------------
 // Cache rows attended: sparse (k_idx != nullptr): k_idx[b,kv,0..k_cnt[b,kv]); dense: 0..kv_lens[b].
 struct AttnArgs {

@@ -12,49 +12,9 @@
 // float32 keys: plain FMA loop, one key per thread, Qbar broadcast from LDS.
 #include "common.hip.h"
 #include "kernels.h"
+#include "score_tile.hip.h"
 
 namespace quoka {
-
-constexpr int kScThreads = 256;
-constexpr int kScTile = 128;  // keys per LDS tile
-
-template <int D, int QB>
-struct ScoreCfg {
-  static constexpr int KS = D / 16;             // MFMA k-steps over head_dim
-  static constexpr int LD = D + 8;              // padded LDS row, elements (16-byte pad: conflict-free b128 reads)
-  static constexpr int CG = D / 8;              // 16-byte chunks per key row
-  static constexpr int RPI = kScThreads / CG;   // key rows covered by one block-wide load
-  static constexpr int NLD = kScTile / RPI;     // loads per thread per tile
-  static constexpr int KG = 4 / QB;             // wave groups that split a tile's keys
-  static constexpr int KPW = kScTile / KG;      // keys per wave per tile
-  static constexpr size_t kTileBytes = (size_t)kScTile * LD * 2;
-  // two K tiles; three generations of squared norms and of per-query-block maxima (a tile's scores are finished
-  // one step after its products, under the next tile's barrier)
-  static constexpr size_t kLdsBytes = 2 * kTileBytes + 3 * kScTile * 4 + 3 * QB * kScTile * 4;
-};
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-
-// Side job of the fused call: all blocks of the launch together clear `words` 32-bit words.
-__device__ __forceinline__ void clear_words(uint32_t* __restrict__ p, uint32_t words) {
-  if (p == nullptr) return;
-  const uint32_t nblk = gridDim.x * gridDim.y * gridDim.z;
-  const uint32_t blk = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-  for (uint32_t i = blk * blockDim.x + threadIdx.x; i < words; i += nblk * blockDim.x) p[i] = 0u;
-}
-
-// sum of squares of the 8 bf16 values of a 16-byte chunk (products of bf16 pairs are exact in float32)
-__device__ __forceinline__ float sumsq_bf16x8(const u32x4& r) {
-  // (the chunk is reinterpreted as a whole: casting single dwords of the vector to bf16 pairs is miscompiled)
-  const bf16x8 v = __builtin_bit_cast(bf16x8, r);
-  float s = 0.f;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const bf16x2_t p = {v[2 * i], v[2 * i + 1]};
-    s = __builtin_amdgcn_fdot2_f32_bf16(p, p, s, false);
-  }
-  return s;
-}
 
 // EXACT: Qbar enters as the three-term split (float32-exact products).  Otherwise it is rounded to bf16 once and
 // only that term is multiplied: a third of the matrix work, scores within 2^-9 * sum|qbar_i| of the exact ones.
@@ -66,7 +26,7 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
                                                            uint32_t* __restrict__ zero, uint32_t zero_words) {
   using Cfg = ScoreCfg<D, QB>;
   clear_words(zero, zero_words);
-  constexpr int KS = Cfg::KS, LD = Cfg::LD, CG = Cfg::CG, RPI = Cfg::RPI, NLD = Cfg::NLD, KPW = Cfg::KPW;
+  constexpr int LD = Cfg::LD, CG = Cfg::CG, RPI = Cfg::RPI, NLD = Cfg::NLD;
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* tile0p = reinterpret_cast<uint16_t*>(smem);
   uint16_t* tile1p = reinterpret_cast<uint16_t*>(smem + Cfg::kTileBytes);
@@ -106,50 +66,16 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
   if (n_tiles > 1) issue(1, RB);
 
   const bool dot_mode = (dm.flags & 1) != 0, mean_mode = (dm.flags & 2) != 0;   // ablation scorers
-  // Query operands: this wave's 32 query rows, split into three bf16 terms.
-  bf16x8 a_hi[KS], a_mid[KS], a_lo[KS];
-  {
-    int r = qb * 32 + li;
-    const bool pad_row = r >= n_keep;
-    r = pad_row ? n_keep - 1 : r;     // padding rows repeat a real query: the max is unchanged (the mean skips them)
-    const float* qrow = qbar + ((size_t)(b * dm.n_kv + kv) * n_keep + r) * D + 8 * hf;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const float4 x0 = *reinterpret_cast<const float4*>(qrow + ks * 16);
-      const float4 x1 = *reinterpret_cast<const float4*>(qrow + ks * 16 + 4);
-      float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-      if (mean_mode && pad_row) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = 0.f;
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const __bf16 h = (__bf16)x[e];
-        a_hi[ks][e] = h;
-        if constexpr (EXACT) {
-          const float r1 = x[e] - (float)h;
-          const __bf16 m = (__bf16)r1;
-          const float r2 = r1 - (float)m;
-          a_mid[ks][e] = m;
-          a_lo[ks][e] = (__bf16)r2;
-        }
-      }
-    }
-  }
+  QueryTerms<D, EXACT> qt;   // this wave's 32 query rows
+  qt.load(qbar + (size_t)(b * dm.n_kv + kv) * n_keep * D, n_keep, qb, li, hf, mean_mode);
 
   // scores of tile `it` from the maxima and squared norms of generation it % 3
   auto finish = [&](int it) {
     if (tid < kScTile) {
       const int key = t_begin + it * kScTile + tid;
-      if (key < T) {
-        const float* sm = smax + (it % 3) * QB * kScTile;
-        float m = sm[tid];
-#pragma unroll
-        for (int j = 1; j < QB; ++j) m = mean_mode ? m + sm[j * kScTile + tid] : fmaxf(m, sm[j * kScTile + tid]);
-        if (mean_mode) m /= (float)n_keep;
-        const float nrm = dot_mode ? 1.0f : fmaxf(sqrtf(ssq[(it % 3) * kScTile + tid]), kNormEps);
-        sc[key] = m / nrm + 0.0f;
-      }
+      if (key < T)
+        sc[key] = tile_score<QB>(smax + (it % 3) * QB * kScTile, ssq + (it % 3) * kScTile, tid, dot_mode, mean_mode,
+                                 n_keep);
     }
   };
 
@@ -161,12 +87,7 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
     for (int i = 0; i < NLD; ++i) {
       const int rl = r0 + RPI * i;
       *reinterpret_cast<u32x4*>(tl + rl * LD + cg * 8) = R[i];
-      float ss = sumsq_bf16x8(R[i]);
-      if constexpr (CG == 16) {
-        ss = row16_sum(ss);   // a key row is exactly one 16-lane DPP row
-      } else {
-        ss = group_sum<CG>(ss);
-      }
+      const float ss = row_sumsq<CG>(R[i]);
       if (cg == 0) ssq_g[rl] = ss;
     }
     // One barrier per tile.  It publishes tile `it` (and its squared norms) and the maxima of tile it-1.  The K tile
@@ -176,51 +97,7 @@ __global__ __launch_bounds__(kScThreads, 2) void score_bf16(Dims dm, const float
     if (it + 2 < n_tiles) issue(it + 2, R);  // the registers are free again: fetch the tile after the next
     if (it > 0) finish(it - 1);
 
-    // Products.  All three query terms go into one accumulator per key block (smallest term first inside every
-    // k-step), so there is nothing to add up afterwards; two key blocks are interleaved to keep the MFMA chains
-    // independent.
-    constexpr int NKB = KPW / 32;
-#pragma unroll
-    for (int kb = 0; kb < NKB; kb += 2) {
-      constexpr int kPair = NKB >= 2 ? 2 : 1;
-      f32x16 c[kPair];
-      const uint16_t* kp[kPair];
-#pragma unroll
-      for (int u = 0; u < kPair; ++u) {
-        c[u] = f32x16{0};
-        kp[u] = tl + (kg * KPW + (kb + u) * 32 + li) * LD + 8 * hf;
-      }
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 kop[kPair];
-#pragma unroll
-        for (int u = 0; u < kPair; ++u) kop[u] = *reinterpret_cast<const bf16x8*>(kp[u] + ks * 16);
-        if constexpr (EXACT) {
-#pragma unroll
-          for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo[ks], kop[u], c[u], 0, 0, 0);
-#pragma unroll
-          for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_mid[ks], kop[u], c[u], 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < kPair; ++u) c[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[ks], kop[u], c[u], 0, 0, 0);
-      }
-#pragma unroll
-      for (int u = 0; u < kPair; ++u) {
-        float m;
-        if (mean_mode) {   // sum over this wave's 32 query rows (padding rows are zero)
-          m = 0.f;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) m += c[u][v];
-          m += other_half(m);
-        } else {
-          m = -INFINITY;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) m = fmaxf(m, c[u][v]);
-          m = fmaxf(m, other_half(m));
-        }
-        if (hf == 0) smax_g[qb * kScTile + kg * KPW + (kb + u) * 32 + li] = m;
-      }
-    }
+    tile_products<D, QB, EXACT>(tl, qt, qb, kg, li, hf, mean_mode, smax_g);
   };
   for (int it = 0; it < n_tiles; it += 2) {
     tile_step(it, RA);

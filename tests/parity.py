@@ -9,6 +9,34 @@ TOL_SCORE = 1e-6   # float32-accumulated cosine-like scores in [-1, 1] vs. the f
 TOL_QBAR = 5e-7
 
 
+def two_pass_scores(w) -> bool:
+    """Whether quoka_select_keys (and so quoka_chunk_attn) takes its two-pass route for this workload: bf16 caches
+    longer than 32768 positions (include/quoka.h).  `scores` then holds exact values near the cut only."""
+    return w.dtype == "bf16" and w.t_max > 32768
+
+
+def check_two_pass_scores(got, want, qbar, budget, what=""):
+    """Scores left by the two-pass stage for one KV head.  got, want: [T] (GPU float32, oracle float64); qbar: the
+    head's [N', d] float32 Q-bar.  Every score is within the proven bound of the provisional pass,
+    max_r ||qbar_r - bf16(qbar_r)||_2 + 4e-6, and the scores that decide the selection -- every key within 2^-11 of
+    the cut, the margin the interface states -- meet the bar of the exact scorer."""
+    from gen.workloads import bf16_round
+    T = want.shape[0]
+    if T == 0:
+        return
+    q = np.asarray(qbar, dtype=np.float32)
+    delta = q.astype(np.float64) - bf16_round(q).astype(np.float64)
+    eps = float(np.sqrt((delta * delta).sum(axis=1)).max()) + 4e-6
+    err = np.abs(np.asarray(got, dtype=np.float64) - want)
+    assert err.max() <= eps, f"{what}: provisional score off by {err.max()} > bound {eps}"
+    Bp = max(0, min(int(budget), T))
+    if 0 < Bp < T:
+        cut = np.sort(want)[T - Bp]
+        near = np.abs(want - cut) <= 2.0 ** -11 - 1e-5
+        assert near.sum() >= 1
+        assert err[near].max() <= TOL_SCORE, f"{what}: score near the cut off by {err[near].max()}"
+
+
 def tie_band(cut: float) -> float:
     return TIE_REL * max(abs(cut), 1e-3)
 
