@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libquoka.so")
 
-SOURCES = ["api.hip", "select_queries.hip", "score_keys.hip", "topk_keys.hip", "select_keys.hip", "attn_mfma.hip", "attn_decode.hip", "attn_f32.hip",
+SOURCES = ["api.hip", "select_queries.hip", "score_keys.hip", "topk_keys.hip", "select_keys.hip", "score_stream.hip", "attn_mfma.hip", "attn_decode.hip", "attn_f32.hip",
            "probes.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -20,7 +20,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 VALU forms are kept off on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-command-line-argument",
+    "-Wno-unused-command-line-argument", "-Wno-inline-asm",   # (m0 is named as clobbered by the LDS-direct loads)
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

@@ -241,10 +241,12 @@ quoka_status quoka_dense_attn(const quoka_shape* shape, const void* q, const voi
 // (whose scoring launch clears the multi-block top-k's histograms).
 static quoka_status select_keys_common(const Dims& dm, int dtype, const float* qbar, const void* k_cache,
                                        const int32_t* kv_lens, const int32_t* budgets, float* scores, int32_t* k_idx,
-                                       int32_t* k_cnt, void* workspace, const WsLayout& l, hipStream_t hs) {
+                                       int32_t* k_cnt, void* workspace, const WsLayout& l, hipStream_t hs,
+                                       bool sel_ws_is_zero) {
   if (dm.T_max > 0 && quoka::select_keys_two_pass_applies(dm, dtype)) {
     uint32_t* sel_ws = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + l.sel_off);
-    return from_hip(quoka::launch_select_keys(dm, qbar, k_cache, kv_lens, budgets, scores, k_idx, k_cnt, sel_ws, hs));
+    return from_hip(quoka::launch_select_keys(dm, qbar, k_cache, kv_lens, budgets, scores, k_idx, k_cnt, sel_ws, hs,
+                                              sel_ws_is_zero));
   }
   uint32_t* topk_ws = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + l.topk_off);
   const size_t topk_words = quoka::topk_ws_words(dm);
@@ -269,7 +271,7 @@ quoka_status quoka_select_keys(const quoka_shape* shape, const float* qbar, cons
   st = check_ws(l, workspace, workspace_bytes);
   if (st != QUOKA_OK) return st;
   return select_keys_common(dm, shape->dtype, qbar, k_cache, kv_lens, budgets, scores, k_idx, k_cnt, workspace, l,
-                            static_cast<hipStream_t>(stream));
+                            static_cast<hipStream_t>(stream), false);
 }
 
 quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const void* k_cache, const void* v_cache,
@@ -277,10 +279,28 @@ quoka_status quoka_chunk_attn(const quoka_shape* shape, const void* q, const voi
                               const void* v_chunk, int32_t* q_idx, float* qbar, float* scores, int32_t* k_idx,
                               int32_t* k_cnt, void* out, float* lse, void* workspace, size_t workspace_bytes,
                               void* stream) {
-  quoka_status st = quoka_select_queries(shape, q, q_idx, qbar, workspace, workspace_bytes, stream);
+  // The stages as in quoka_select_queries / quoka_select_keys (same checks), except that the last launch of the query
+  // stage also clears the histograms and counters of the two-pass key selection, which saves that stage a launch.
+  Dims dm;
+  quoka_status st = check_shape(shape, &dm);
   if (st != QUOKA_OK) return st;
-  st = quoka_select_keys(shape, qbar, k_cache, kv_lens, budgets, scores, k_idx, k_cnt, workspace, workspace_bytes,
-                         stream);
+  if (q == nullptr || q_idx == nullptr || qbar == nullptr) return QUOKA_EINVAL;
+  if (kv_lens == nullptr || budgets == nullptr || k_cnt == nullptr) return QUOKA_EINVAL;
+  if (dm.T_max > 0 && (k_cache == nullptr || scores == nullptr)) return QUOKA_EINVAL;
+  if (dm.B_max > 0 && k_idx == nullptr) return QUOKA_EINVAL;
+  if (!aligned16(q) || !aligned16(qbar) || !aligned16(k_cache)) return QUOKA_EINVAL;
+  const WsLayout l = layout(dm);
+  st = check_ws(l, workspace, workspace_bytes);
+  if (st != QUOKA_OK) return st;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const bool two_pass = dm.T_max > 0 && quoka::select_keys_two_pass_applies(dm, shape->dtype);
+  uint32_t* sel_ws = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + l.sel_off);
+  float* sq_ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + l.select_off);
+  st = from_hip(quoka::launch_select_queries(dm, shape->dtype, q, q_idx, qbar, sq_ws, hs, two_pass ? sel_ws : nullptr,
+                                             two_pass ? quoka::select_keys_zero_words(dm) : 0));
+  if (st != QUOKA_OK) return st;
+  st = select_keys_common(dm, shape->dtype, qbar, k_cache, kv_lens, budgets, scores, k_idx, k_cnt, workspace, l, hs,
+                          two_pass);
   if (st != QUOKA_OK) return st;
   return quoka_sparse_attn(shape, q, k_cache, v_cache, k_idx, k_cnt, k_chunk, v_chunk, out, lse, workspace,
                            workspace_bytes, stream);

@@ -26,8 +26,10 @@ inline hipError_t ensure_dynamic_lds(const void* func, size_t bytes, std::atomic
 
 // --- query sub-selection (select_queries.hip) -------------------------------------------------
 size_t select_queries_ws_floats(const Dims& dm);
+// `zero` / `zero_words`: optional side job for the fused call -- the last launch clears that many 32-bit words (what
+// the key-selection stage that follows needs cleared).
 hipError_t launch_select_queries(const Dims& dm, int dtype, const void* q, int32_t* q_idx, float* qbar, float* ws,
-                                 hipStream_t st);
+                                 hipStream_t st, uint32_t* zero = nullptr, size_t zero_words = 0);
 
 // --- key scoring (score_keys.hip) ---------------------------------------------------------------
 // `zero` / `zero_words`: optional side job for the fused call -- the scoring blocks clear that many 32-bit words (the
@@ -45,6 +47,8 @@ hipError_t launch_topk_keys(const Dims& dm, const float* scores, const int32_t* 
 // Provisional one-term scores, exact re-scoring of the keys near the cut, ordered emission: the same index lists as
 // launch_score_keys followed by launch_topk_keys.  `ws_is_zero`: the first select_keys_zero_words words of the
 // workspace have already been cleared on this stream.
+hipError_t launch_score_stream(const Dims& dm, const float* qbar, const void* k_cache, const int32_t* kv_lens,
+                               float* scores, uint32_t* hist_ws, hipStream_t st);
 bool select_keys_two_pass_applies(const Dims& dm, int dtype);
 size_t select_keys_ws_words(const Dims& dm);
 size_t select_keys_zero_words(const Dims& dm);

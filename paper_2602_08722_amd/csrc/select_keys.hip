@@ -15,56 +15,15 @@
 // The selected set is therefore exactly the top-B of the exact scores, as the separate scoring and top-B calls
 // produce it; the `scores` array ends up holding exact values inside the band and provisional values elsewhere.
 //
-// Launch chain (no block ever waits for another block of its launch): provisional scoring, histogram, band
-// classification + exact re-scoring per 2048-key tile, one block per head that selects among the band candidates
-// and lays out the tiles' output offsets, ordered emission per tile.
+// Launch chain (no block ever waits for another block of its launch): provisional scoring with the histogram
+// (score_stream.hip), band classification + exact re-scoring per 2048-key tile, one block per head that selects
+// among the band candidates and lays out the tiles' output offsets, ordered emission per tile.
 #include "common.hip.h"
 #include "kernels.h"
 #include "score_tile.hip.h"
+#include "select_ws.hip.h"
 
 namespace quoka {
-
-constexpr int kSelBins = 4096;        // equal bins over [-1, 1]
-constexpr int kSelTile = 2048;        // keys per block in the per-tile kernels
-constexpr int kSelThreads = 256;
-constexpr int kSelIPT = kSelTile / kSelThreads;
-constexpr int kSelMeta = 16;          // per-head words: candidate count, band limits, exact cut
-constexpr int kSelHeadThreads = 1024;
-constexpr int kSelMaxTiles = (1 << 24) / kSelTile;   // the interface limits a cache to 2^24 - 1 positions
-
-enum { kMetaCand = 0, kMetaBinLo = 1, kMetaBinHi = 2, kMetaTau = 3, kMetaNeedEq = 4 };
-
-// Bin of a provisional score: monotone in p, the same expression wherever it is evaluated.
-__device__ __forceinline__ int score_bin(float p) {
-  const float x = (p + 1.0f) * (float)(kSelBins / 2);
-  return min(max((int)floorf(x), 0), kSelBins - 1);
-}
-
-// Workspace of the stage.  The words that must be zero when the chain starts (histograms and candidate counters of
-// all heads) come first, in one contiguous run, so that an earlier launch can clear them as a side job.
-struct SelWs {
-  uint32_t *hist, *meta, *tile_in, *tile_off, *tile_eqb, *mask, *cand_key, *cand_pos;
-};
-__host__ __device__ inline int sel_tiles(int T_max) { return (T_max + kSelTile - 1) / kSelTile; }
-__host__ __device__ inline size_t sel_mask_words(int T_max) { return (size_t)sel_tiles(T_max) * (kSelTile / 32); }
-__host__ __device__ inline size_t sel_zero_words(int heads) { return (size_t)heads * (kSelBins + kSelMeta); }
-__host__ __device__ inline size_t sel_head_words(int T_max) {
-  return 3 * (size_t)sel_tiles(T_max) + sel_mask_words(T_max) + 2 * (size_t)T_max;
-}
-__device__ __forceinline__ SelWs sel_ws(uint32_t* ws, int heads, int head, int T_max) {
-  SelWs s;
-  s.hist = ws + (size_t)head * (kSelBins + kSelMeta);
-  s.meta = s.hist + kSelBins;
-  uint32_t* p = ws + sel_zero_words(heads) + (size_t)head * sel_head_words(T_max);
-  const int nt = sel_tiles(T_max);
-  s.tile_in = p;
-  s.tile_off = p + nt;
-  s.tile_eqb = p + 2 * nt;
-  s.mask = p + 3 * nt;
-  s.cand_key = s.mask + sel_mask_words(T_max);
-  s.cand_pos = s.cand_key + T_max;
-  return s;
-}
 
 struct SelCtx {
   int T, B, head;
@@ -87,34 +46,15 @@ __global__ void sel_zero(uint32_t* __restrict__ p, size_t n) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Histogram of the provisional scores of one tile (LDS histogram, integer-atomic flush of the occupied bins).
-__global__ __launch_bounds__(kSelThreads) void sel_hist(Dims dm, float* __restrict__ scores,
-                                                       const int32_t* __restrict__ kv_lens,
-                                                       const int32_t* __restrict__ budgets, uint32_t* __restrict__ ws) {
-  __shared__ uint32_t lh[kSelBins];
-  const SelCtx c = sel_ctx(dm, scores, kv_lens, budgets, ws, blockIdx.y, blockIdx.z);
-  const int t0 = blockIdx.x * kSelTile;
-  if (c.B == 0 || c.B >= c.T || t0 >= c.T) return;   // block-uniform: nothing to select, or everything
-  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) lh[i] = 0u;
-  __syncthreads();
-  const int t1 = min(t0 + kSelTile, c.T);
-  for (int t = t0 + threadIdx.x; t < t1; t += kSelThreads) atomicAdd(&lh[score_bin(c.sc[t])], 1u);
-  __syncthreads();
-  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) {
-    const uint32_t v = lh[i];
-    if (v) atomicAdd(&c.w.hist[i], v);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Per tile: locate the band from the finished histogram, classify the tile's keys, score the band keys exactly.
+// Band classification and exact re-scoring.  A block takes `tpb` consecutive 2048-key tiles of one head: it locates
+// the band once from the finished histogram, then per tile classifies the keys and scores the band keys exactly.
 template <int D, int QB>
 __global__ __launch_bounds__(kSelThreads) void sel_band_rescore(Dims dm, const float* __restrict__ qbar,
                                                                const uint16_t* __restrict__ kc,
                                                                const int32_t* __restrict__ kv_lens,
                                                                const int32_t* __restrict__ budgets,
                                                                float* __restrict__ scores, uint32_t* __restrict__ ws,
-                                                               int n_keep) {
+                                                               int n_keep, int tpb) {
   using Cfg = ScoreCfg<D, QB>;
   constexpr int LD = Cfg::LD, CG = Cfg::CG, RPI = Cfg::RPI, NLD = Cfg::NLD;
   __shared__ __align__(16) uint16_t tile[kScTile * LD];
@@ -122,35 +62,45 @@ __global__ __launch_bounds__(kSelThreads) void sel_band_rescore(Dims dm, const f
   __shared__ float smax[QB * kScTile];
   __shared__ uint32_t band_loc[kSelTile];        // positions (relative to the tile) of the band keys, any order
   __shared__ uint32_t sh[kSelThreads + 2];
-  __shared__ float red[kSelThreads / 64];
-  __shared__ uint32_t bc[4];                     // cut bin, band count, sure-in count, candidate slot base
+  __shared__ uint32_t bc[2];                     // cut bin, candidate slot base
+  __shared__ uint32_t cnt2[2][2];                // per tile parity: band count, sure-in count
 
   const int kv = blockIdx.y, b = blockIdx.z;
   const SelCtx c = sel_ctx(dm, scores, kv_lens, budgets, ws, kv, b);
-  const int t0 = blockIdx.x * kSelTile;
-  if (c.B == 0 || c.B >= c.T || t0 >= c.T) return;   // block-uniform
+  const int tile_first = blockIdx.x * tpb;
+  if (c.B == 0 || c.B >= c.T || tile_first * kSelTile >= c.T) return;   // block-uniform
+  const int tile_end = min(tile_first + tpb, (c.T + kSelTile - 1) / kSelTile);
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  if (tid < 4) bc[tid] = 0u;
+  const int qb = w % QB, kg = w / QB;
+  const int li = lane & 31, hf = lane >> 5;
+  if (tid < 4) (&cnt2[0][0])[tid] = 0u;
 
-  // provisional scores of the tile, requested before anything else (position t0 + tid + 256 * i: coalesced rows)
+  // Everything the block needs from memory before it can classify is requested up front: the first tile's
+  // provisional scores, the histogram, the error bound, and the query operands of the exact product.
   float p[kSelIPT];
+  auto load_p = [&](int t0) __attribute__((always_inline)) {
 #pragma unroll
-  for (int i = 0; i < kSelIPT; ++i) {
-    const int t = t0 + tid + kSelThreads * i;
-    p[i] = t < c.T ? c.sc[t] : 0.f;
+    for (int i = 0; i < kSelIPT; ++i) {
+      const int t = t0 + tid + kSelThreads * i;   // coalesced rows
+      p[i] = t < c.T ? c.sc[t] : 0.f;
+    }
+  };
+  load_p(tile_first * kSelTile);
+  constexpr uint32_t per = kSelBins / kSelThreads;
+  const uint32_t top = kSelBins - tid * per;   // exclusive upper bin of this thread's run (thread 0: highest bins)
+  uint32_t hv[per];
+#pragma unroll
+  for (uint32_t i = 0; i < per; i += 4) {
+    const u32x4 v = *reinterpret_cast<const u32x4*>(c.w.hist + top - per + i);
+    hv[i] = v[0]; hv[i + 1] = v[1]; hv[i + 2] = v[2]; hv[i + 3] = v[3];
   }
+  const float d2 = __uint_as_float(c.w.meta[kMetaEps2]);
+  QueryTerms<D, true> qt;
+  qt.load(qbar + (size_t)c.head * n_keep * D, n_keep, qb, li, hf, false);
 
   // ---- the bin of the provisional cut: scanning from the top, where the running count reaches B ----
   {
-    constexpr uint32_t per = kSelBins / kSelThreads;
-    const uint32_t top = kSelBins - tid * per;   // exclusive upper bin of this thread's run (thread 0: highest bins)
-    uint32_t hv[per];
-#pragma unroll
-    for (uint32_t i = 0; i < per; i += 4) {
-      const u32x4 v = *reinterpret_cast<const u32x4*>(c.w.hist + top - per + i);
-      hv[i] = v[0]; hv[i + 1] = v[1]; hv[i + 2] = v[2]; hv[i + 3] = v[3];
-    }
     uint32_t mine = 0;
 #pragma unroll
     for (uint32_t i = 0; i < per; ++i) mine += hv[i];
@@ -173,36 +123,9 @@ __global__ __launch_bounds__(kSelThreads) void sel_band_rescore(Dims dm, const f
       bc[0] = top - per + (uint32_t)max(found, 0);
     }
   }
-
-  // ---- eps: the largest distance between a row of Qbar and its bf16 rounding ----
-  float d2 = 0.f;
-  {
-    const float* qh = qbar + (size_t)c.head * n_keep * D;
-    const int cgq = tid % CG, rq = tid / CG;
-    for (int r0 = 0; r0 < n_keep; r0 += kSelThreads / CG) {   // uniform trip count; rows past the end repeat the last
-      const int r = min(r0 + rq, n_keep - 1);
-      const float4 x0 = *reinterpret_cast<const float4*>(qh + (size_t)r * D + cgq * 8);
-      const float4 x1 = *reinterpret_cast<const float4*>(qh + (size_t)r * D + cgq * 8 + 4);
-      const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-      float s = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float dlt = x[e] - (float)(__bf16)x[e];
-        s += dlt * dlt;
-      }
-      if constexpr (CG == 16) {
-        s = row16_sum(s);
-      } else {
-        s = group_sum<CG>(s);
-      }
-      d2 = fmaxf(d2, s);
-    }
-    d2 = wave64_max(d2);
-    if (lane == 0) red[w] = d2;
-  }
   __syncthreads();
-  d2 = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  // |p - s| <= ||delta|| (exact arithmetic) + float32 accumulation and bin-edge slack of the two computed values
+  // |p - s| <= ||delta|| (exact arithmetic; the scoring launch left the largest squared ||delta|| of the head) plus
+  // the float32 accumulation and bin-edge slack of the two computed values
   const float eps = sqrtf(d2) * 1.001f + 4e-6f;
   const int m = (int)ceilf(2.0f * eps * (float)(kSelBins / 2)) + 1;
   const int cut_bin = (int)bc[0];
@@ -211,74 +134,76 @@ __global__ __launch_bounds__(kSelThreads) void sel_band_rescore(Dims dm, const f
     c.w.meta[kMetaBinLo] = (uint32_t)bin_lo;
     c.w.meta[kMetaBinHi] = (uint32_t)bin_hi;
   }
-
-  // ---- classify: certainly selected (counted), band (listed, flagged in the mask), certainly not ----
-  uint32_t n_in = 0;
-#pragma unroll
-  for (int i = 0; i < kSelIPT; ++i) {
-    const int tl = tid + kSelThreads * i;
-    const bool valid = t0 + tl < c.T;
-    const int bin = score_bin(p[i]);
-    const bool inb = valid && bin >= bin_lo && bin <= bin_hi;
-    n_in += (valid && bin > bin_hi) ? 1u : 0u;
-    const unsigned long long bal = __builtin_amdgcn_ballot_w64(inb);
-    // positions tl of one wave in one round are 64 consecutive keys: its ballot is two words of the tile's mask
-    if (lane == 0) {
-      uint32_t* mw = c.w.mask + (size_t)blockIdx.x * (kSelTile / 32) + (kSelThreads * i + 64 * w) / 32;
-      mw[0] = (uint32_t)bal;
-      mw[1] = (uint32_t)(bal >> 32);
-    }
-    uint32_t base = 0;
-    if (lane == 0 && bal != 0) base = atomicAdd(&bc[1], (uint32_t)__popcll(bal));
-    base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-    if (inb) band_loc[base + __popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)tl;
-  }
-  n_in = wave_incl_scan_u32(n_in);
-  if (lane == 63 && n_in) atomicAdd(&bc[2], n_in);
-  __syncthreads();
-  const int n_band = (int)bc[1];
-  if (tid == 0) {
-    c.w.tile_in[blockIdx.x] = bc[2];
-    if (n_band > 0) bc[3] = atomicAdd(&c.w.meta[kMetaCand], (uint32_t)n_band);   // slots in the head's candidate list
-  }
-  if (n_band == 0) return;   // block-uniform
-  __syncthreads();
-  const uint32_t slot0 = bc[3];
-
-  // ---- exact scores of the band keys, 128 at a time, by the tile arithmetic of the streaming kernel ----
-  const int qb = w % QB, kg = w / QB;
-  const int li = lane & 31, hf = lane >> 5;
-  QueryTerms<D, true> qt;
-  qt.load(qbar + (size_t)c.head * n_keep * D, n_keep, qb, li, hf, false);
   const char* kbase = reinterpret_cast<const char*>(kc + b * dm.kvs[0] + kv * dm.kvs[1]);
   const uint32_t row_bytes = (uint32_t)dm.kvs[2] * 2u;
   const int cg = tid % CG, r0 = tid / CG;
-  for (int j0 = 0; j0 < n_band; j0 += kScTile) {
-    u32x4 R[NLD];
+
+  for (int tile_i = tile_first; tile_i < tile_end; ++tile_i) {
+    const int t0 = tile_i * kSelTile;
+    // ---- classify: certainly selected (counted), band (listed, flagged in the mask), certainly not ----
+    uint32_t n_in = 0;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int j = min(j0 + r0 + RPI * i, n_band - 1);   // tail slots repeat a real row; their scores are not used
-      const uint32_t row = (uint32_t)t0 + band_loc[j];
-      R[i] = *reinterpret_cast<const u32x4*>(kbase + (row * row_bytes + (uint32_t)cg * 16u));
+    for (int i = 0; i < kSelIPT; ++i) {
+      const int tl = tid + kSelThreads * i;
+      const bool valid = t0 + tl < c.T;
+      const int bin = score_bin(p[i]);
+      const bool inb = valid && bin >= bin_lo && bin <= bin_hi;
+      n_in += (valid && bin > bin_hi) ? 1u : 0u;
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(inb);
+      // positions tl of one wave in one round are 64 consecutive keys: its ballot is two words of the tile's mask
+      if (lane == 0) {
+        uint32_t* mw = c.w.mask + (size_t)tile_i * (kSelTile / 32) + (kSelThreads * i + 64 * w) / 32;
+        mw[0] = (uint32_t)bal;
+        mw[1] = (uint32_t)(bal >> 32);
+      }
+      uint32_t base = 0;
+      if (lane == 0 && bal != 0) base = atomicAdd(&cnt2[tile_i & 1][0], (uint32_t)__popcll(bal));
+      base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+      if (inb) band_loc[base + __popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)tl;
     }
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int rl = r0 + RPI * i;
-      *reinterpret_cast<u32x4*>(tile + rl * LD + cg * 8) = R[i];
-      const float ss = row_sumsq<CG>(R[i]);
-      if (cg == 0) ssq[rl] = ss;
+    if (tile_i + 1 < tile_end) load_p(t0 + kSelTile);   // the next tile's scores travel during the re-scoring
+    n_in = wave_incl_scan_u32(n_in);
+    if (lane == 63 && n_in) atomicAdd(&cnt2[tile_i & 1][1], n_in);
+    __syncthreads();
+    const int n_band = (int)cnt2[tile_i & 1][0];
+    if (tid == 0) {
+      c.w.tile_in[tile_i] = cnt2[tile_i & 1][1];
+      if (n_band > 0) bc[1] = atomicAdd(&c.w.meta[kMetaCand], (uint32_t)n_band);   // slots in the head's candidate list
+      // the other parity's counters serve the next tile: their last readers passed the previous tile's second barrier
+      cnt2[(tile_i + 1) & 1][0] = 0u;
+      cnt2[(tile_i + 1) & 1][1] = 0u;
     }
     __syncthreads();
-    tile_products<D, QB, true>(tile, qt, qb, kg, li, hf, false, smax);
-    __syncthreads();
-    if (tid < kScTile && j0 + tid < n_band) {
-      const float s = tile_score<QB>(smax, ssq, tid, false, false, n_keep);
-      const uint32_t pos = (uint32_t)t0 + band_loc[j0 + tid];
-      c.sc[pos] = s;
-      c.w.cand_key[slot0 + j0 + tid] = max(okey(s), 1u);
-      c.w.cand_pos[slot0 + j0 + tid] = pos;
+    const uint32_t slot0 = bc[1];
+
+    // ---- exact scores of the band keys, 128 at a time, by the tile arithmetic of the streaming kernel ----
+    for (int j0 = 0; j0 < n_band; j0 += kScTile) {
+      u32x4 R[NLD];
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int j = min(j0 + r0 + RPI * i, n_band - 1);   // tail slots repeat a real row; their scores are not used
+        const uint32_t row = (uint32_t)t0 + band_loc[j];
+        R[i] = *reinterpret_cast<const u32x4*>(kbase + (row * row_bytes + (uint32_t)cg * 16u));
+      }
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int rl = r0 + RPI * i;
+        *reinterpret_cast<u32x4*>(tile + rl * LD + cg * 8) = R[i];
+        const float ss = row_sumsq<CG>(R[i]);
+        if (cg == 0) ssq[rl] = ss;
+      }
+      __syncthreads();
+      tile_products<D, QB, true>(tile, qt, qb, kg, li, hf, false, smax);
+      __syncthreads();
+      if (tid < kScTile && j0 + tid < n_band) {
+        const float s = tile_score<QB>(smax, ssq, tid, false, false, n_keep);
+        const uint32_t pos = (uint32_t)t0 + band_loc[j0 + tid];
+        c.sc[pos] = s;
+        c.w.cand_key[slot0 + j0 + tid] = max(okey(s), 1u);
+        c.w.cand_pos[slot0 + j0 + tid] = pos;
+      }
+      __syncthreads();   // the tile, norms and maxima are overwritten by the next batch (and band_loc by the next tile)
     }
-    __syncthreads();   // the tile, norms and maxima are overwritten by the next batch
   }
 }
 
@@ -287,13 +212,12 @@ __global__ __launch_bounds__(kSelThreads) void sel_band_rescore(Dims dm, const f
 // Radix select (descending) over keys that are read again from memory in every pass (the candidate list of a head is
 // a few tens of KiB and stays in cache; there is no bound on its length, so registers cannot hold it in general).
 struct HeadSelectLds {
-  uint32_t hist[3][256];
-  uint32_t wmin[16], wmax[16];
+  RadixSelectLds rs;
   uint32_t wsum[kSelHeadThreads / 64 + 1];
 };
 
 __device__ __forceinline__ void stream_radix_select_desc(const uint32_t* __restrict__ keys, uint32_t n, uint32_t need,
-                                                         HeadSelectLds& L, uint32_t* cut_key, uint32_t* need_eq) {
+                                                         RadixSelectLds& L, uint32_t* cut_key, uint32_t* need_eq) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   if (tid < 768) (&L.hist[0][0])[tid] = 0u;
   uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
@@ -383,10 +307,28 @@ __global__ __launch_bounds__(kSelHeadThreads) void sel_band_select(Dims dm, floa
   for (int i = tid; i < nt; i += kSelHeadThreads) cnt[i] = 0u;
   __syncthreads();
   uint32_t tau, need_eq;
-  stream_radix_select_desc(c.w.cand_key, n_c, need, L, &tau, &need_eq);
-  for (uint32_t i = tid; i < n_c; i += kSelHeadThreads) {
-    const uint32_t k = c.w.cand_key[i];
-    if (k >= tau) atomicAdd(&cnt[c.w.cand_pos[i] / kSelTile], k > tau ? 0x10000u : 1u);
+  constexpr int kRegIPT = 16;
+  if (n_c <= (uint32_t)(kSelHeadThreads * kRegIPT)) {   // block-uniform; the usual case: the candidates fit registers
+    uint32_t key[kRegIPT], pos[kRegIPT];
+    uint32_t valid = 0u;
+#pragma unroll
+    for (int j = 0; j < kRegIPT; ++j) {
+      const uint32_t i = (uint32_t)tid + (uint32_t)kSelHeadThreads * j;
+      const bool in = i < n_c;
+      key[j] = in ? c.w.cand_key[i] : 0u;   // real keys are never 0
+      pos[j] = in ? c.w.cand_pos[i] : 0u;
+      valid |= (in ? 1u : 0u) << j;
+    }
+    block_radix_select<kRegIPT, true>(key, valid, need, L.rs, &tau, &need_eq);
+#pragma unroll
+    for (int j = 0; j < kRegIPT; ++j)
+      if (((valid >> j) & 1u) && key[j] >= tau) atomicAdd(&cnt[pos[j] / kSelTile], key[j] > tau ? 0x10000u : 1u);
+  } else {
+    stream_radix_select_desc(c.w.cand_key, n_c, need, L.rs, &tau, &need_eq);
+    for (uint32_t i = tid; i < n_c; i += kSelHeadThreads) {
+      const uint32_t k = c.w.cand_key[i];
+      if (k >= tau) atomicAdd(&cnt[c.w.cand_pos[i] / kSelTile], k > tau ? 0x10000u : 1u);
+    }
   }
   __syncthreads();
   // Output offsets.  Thread t owns tiles t*tpt .. +tpt; first the number of cut-equal band keys before every tile
@@ -499,19 +441,23 @@ size_t select_keys_zero_words(const Dims& dm) { return sel_zero_words(dm.b * dm.
 
 template <int D>
 static void launch_rescore(const Dims& dm, const float* qbar, const void* kc, const int32_t* kv_lens,
-                           const int32_t* budgets, float* scores, uint32_t* ws, int n_keep, dim3 grid,
-                           hipStream_t st) {
+                           const int32_t* budgets, float* scores, uint32_t* ws, int n_keep, hipStream_t st) {
+  // about three blocks per compute unit: fewer, fatter blocks amortise the histogram scan and the query operands
+  const int heads = dm.b * dm.n_kv, nt = sel_tiles(dm.T_max);
+  const int per_head = (768 + heads - 1) / heads;
+  const int tpb = (nt + per_head - 1) / per_head;
+  const dim3 grid((nt + tpb - 1) / tpb, dm.n_kv, dm.b);
   const int qblocks = (n_keep + 31) / 32;
   const uint16_t* k = static_cast<const uint16_t*>(kc);
   if (qblocks <= 1) {
     hipLaunchKernelGGL((sel_band_rescore<D, 1>), grid, dim3(kSelThreads), 0, st, dm, qbar, k, kv_lens, budgets, scores,
-                       ws, n_keep);
+                       ws, n_keep, tpb);
   } else if (qblocks == 2) {
     hipLaunchKernelGGL((sel_band_rescore<D, 2>), grid, dim3(kSelThreads), 0, st, dm, qbar, k, kv_lens, budgets, scores,
-                       ws, n_keep);
+                       ws, n_keep, tpb);
   } else {
     hipLaunchKernelGGL((sel_band_rescore<D, 4>), grid, dim3(kSelThreads), 0, st, dm, qbar, k, kv_lens, budgets, scores,
-                       ws, n_keep);
+                       ws, n_keep, tpb);
   }
 }
 
@@ -520,17 +466,14 @@ hipError_t launch_select_keys(const Dims& dm, const float* qbar, const void* k_c
                               hipStream_t st, bool ws_is_zero) {
   const int n_keep = dm.n_ret < dm.C ? dm.n_ret : dm.C;
   if (!ws_is_zero) hipLaunchKernelGGL(sel_zero, dim3(64), dim3(256), 0, st, ws, select_keys_zero_words(dm));
-  // provisional scores: the streaming kernel with the single bf16 term
-  Dims prov = dm;
-  prov.flags |= QUOKA_SCORE_QBAR_BF16;
-  hipError_t e = launch_score_keys(prov, QUOKA_BF16, qbar, k_cache, kv_lens, scores, st);
+  // provisional scores and their histogram in one streaming launch
+  hipError_t e = launch_score_stream(dm, qbar, k_cache, kv_lens, scores, ws, st);
   if (e != hipSuccess) return e;
   const dim3 grid(sel_tiles(dm.T_max), dm.n_kv, dm.b);
-  hipLaunchKernelGGL(sel_hist, grid, dim3(kSelThreads), 0, st, dm, scores, kv_lens, budgets, ws);
   if (dm.d == 64) {
-    launch_rescore<64>(dm, qbar, k_cache, kv_lens, budgets, scores, ws, n_keep, grid, st);
+    launch_rescore<64>(dm, qbar, k_cache, kv_lens, budgets, scores, ws, n_keep, st);
   } else {
-    launch_rescore<128>(dm, qbar, k_cache, kv_lens, budgets, scores, ws, n_keep, grid, st);
+    launch_rescore<128>(dm, qbar, k_cache, kv_lens, budgets, scores, ws, n_keep, st);
   }
   hipLaunchKernelGGL(sel_band_select, dim3(dm.n_kv, dm.b), dim3(kSelHeadThreads), 0, st, dm, scores, kv_lens, budgets,
                      ws);

@@ -11,6 +11,7 @@
 //                     group and average                                                 -> qbar
 #include "common.hip.h"
 #include "kernels.h"
+#include "score_tile.hip.h"
 
 namespace quoka {
 
@@ -204,8 +205,10 @@ constexpr int kGroupUnroll = 8;
 enum { kFromIndex = 0, kIdentity = 1, kUniform = 2 };
 template <typename T, int D, int RULE>
 __global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, int32_t* __restrict__ q_idx,
-                                             float* __restrict__ qbar, int n_keep) {
+                                             float* __restrict__ qbar, int n_keep, uint32_t* __restrict__ zero,
+                                             uint32_t zero_words) {
   constexpr int EPL = D / 64;
+  clear_words(zero, zero_words);   // side job of the fused call: histograms and counters of the key-selection stage
   const int r = blockIdx.x, kv = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x;
   float acc[EPL];
@@ -253,14 +256,14 @@ __global__ __launch_bounds__(64) void sq_qbar(Dims dm, const T* __restrict__ q, 
 // ---------------------------------------------------------------------------------------------
 template <typename T, int D>
 static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, float* qbar, float* ws_part,
-                               float* ws_cos, hipStream_t st) {
+                               float* ws_cos, hipStream_t st, uint32_t* zero, uint32_t zero_words) {
   const int n_keep = dm.n_ret < dm.C ? dm.n_ret : dm.C;
   const T* qp = static_cast<const T*>(q);
   const dim3 qgrid(n_keep, dm.n_kv, dm.b);
   if (dm.C <= dm.n_ret) {
-    hipLaunchKernelGGL((sq_qbar<T, D, kIdentity>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
+    hipLaunchKernelGGL((sq_qbar<T, D, kIdentity>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep, zero, zero_words);
   } else if (dm.flags & QUOKA_SELECT_UNIFORM) {
-    hipLaunchKernelGGL((sq_qbar<T, D, kUniform>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
+    hipLaunchKernelGGL((sq_qbar<T, D, kUniform>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep, zero, zero_words);
   } else {
     const int n_tiles = (dm.C + kSqTile - 1) / kSqTile;
     dim3 grid(n_tiles, dm.n_q, dm.b);
@@ -277,7 +280,7 @@ static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, fl
     } else {
       hipLaunchKernelGGL((sq_select<8>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
     }
-    hipLaunchKernelGGL((sq_qbar<T, D, kFromIndex>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep);
+    hipLaunchKernelGGL((sq_qbar<T, D, kFromIndex>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep, zero, zero_words);
   }
   return hipGetLastError();
 }
@@ -288,16 +291,17 @@ size_t select_queries_ws_floats(const Dims& dm) {
 }
 
 hipError_t launch_select_queries(const Dims& dm, int dtype, const void* q, int32_t* q_idx, float* qbar, float* ws,
-                                 hipStream_t st) {
+                                 hipStream_t st, uint32_t* zero, size_t zero_words_sz) {
+  const uint32_t zero_words = (uint32_t)zero_words_sz;
   const size_t n_tiles = (dm.C + kSqTile - 1) / kSqTile;
   float* ws_part = ws;
   float* ws_cos = ws + (size_t)dm.b * dm.n_q * n_tiles * dm.d;
   if (dtype == QUOKA_F32) {
-    return dm.d == 64 ? launch_typed<float, 64>(dm, q, q_idx, qbar, ws_part, ws_cos, st)
-                      : launch_typed<float, 128>(dm, q, q_idx, qbar, ws_part, ws_cos, st);
+    return dm.d == 64 ? launch_typed<float, 64>(dm, q, q_idx, qbar, ws_part, ws_cos, st, zero, zero_words)
+                      : launch_typed<float, 128>(dm, q, q_idx, qbar, ws_part, ws_cos, st, zero, zero_words);
   }
-  return dm.d == 64 ? launch_typed<uint16_t, 64>(dm, q, q_idx, qbar, ws_part, ws_cos, st)
-                    : launch_typed<uint16_t, 128>(dm, q, q_idx, qbar, ws_part, ws_cos, st);
+  return dm.d == 64 ? launch_typed<uint16_t, 64>(dm, q, q_idx, qbar, ws_part, ws_cos, st, zero, zero_words)
+                    : launch_typed<uint16_t, 128>(dm, q, q_idx, qbar, ws_part, ws_cos, st, zero, zero_words);
 }
 
 }  // namespace quoka
