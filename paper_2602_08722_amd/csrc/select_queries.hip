@@ -7,6 +7,8 @@
 //                     result is bit-reproducible), then CosSim(q_i, M_Q) for the tile   -> ws.cos
 //   sq_select       : per (b, q-head) the N' lowest cosines in rank order (radix select on register-held
 //                     keys + rank by counting)                                          -> q_idx
+//   sq_head_select  : the three steps above in one block per (b, q-head), for batches of short chunks (the rows of
+//                     a head fit the block's registers and the heads alone fill the chip)
 //   sq_qbar         : per (b, KV head, r) unit-normalise the r-th retained query of each head of the
 //                     group and average                                                 -> qbar
 #include "common.hip.h"
@@ -118,27 +120,13 @@ __global__ __launch_bounds__(kSqThreads) void sq_cosine(Dims dm, const T* __rest
 constexpr int kMaxKeep = 128;
 constexpr int kSelThreads = 1024;
 
+// The N' lowest keys of a block's register-held order-preserving keys, in rank order, to out[0..n_keep): radix select,
+// compaction of the retained ones in position order, rank by counting.  Thread t holds positions lo .. lo+IPT-1.
 template <int IPT>
-__global__ __launch_bounds__(kSelThreads) void sq_select(Dims dm, const float* __restrict__ cosv,
-                                                        int32_t* __restrict__ q_idx, int n_keep) {
-  constexpr int NW = kSelThreads / 64;
-  __shared__ RadixSelectLds rs;
-  __shared__ uint32_t wsum[NW + 1];
-  __shared__ uint32_t sel_key[kMaxKeep];
-  __shared__ uint32_t sel_idx[kMaxKeep];
-  const int h = blockIdx.x, b = blockIdx.y;
-  const int C = dm.C;
+__device__ __forceinline__ void select_lowest_ranked(const uint32_t (&key)[IPT], uint32_t valid, int lo, int n_keep,
+                                                     RadixSelectLds& rs, uint32_t* wsum, uint32_t* sel_key,
+                                                     uint32_t* sel_idx, int32_t* __restrict__ out) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const float* cv = cosv + (size_t)(b * dm.n_q + h) * C;
-  const int lo = tid * IPT;
-  uint32_t key[IPT];
-  uint32_t valid = 0u;
-#pragma unroll
-  for (int j = 0; j < IPT; ++j) {
-    const bool in = lo + j < C;
-    key[j] = in ? okey(cv[lo + j]) : 0xFFFFFFFFu;
-    valid |= (in ? 1u : 0u) << j;
-  }
   // tau: key of the n_keep-th smallest cosine; need_eq: how many elements equal to it are kept (lowest positions first)
   uint32_t tau, need_eq;
   block_radix_select<IPT, false>(key, valid, (uint32_t)n_keep, rs, &tau, &need_eq);
@@ -192,7 +180,153 @@ __global__ __launch_bounds__(kSelThreads) void sq_select(Dims dm, const float* _
     const int w0 = (e * P) >> 6;
     for (int i = 0; i < P / 64; ++i) rank += (int)wsum[w0 + i];
   }
-  if (e < n_keep && part == 0) q_idx[(size_t)(b * dm.n_q + h) * n_keep + rank] = (int32_t)sel_idx[e];
+  if (e < n_keep && part == 0) out[rank] = (int32_t)sel_idx[e];
+}
+
+template <int IPT>
+__global__ __launch_bounds__(kSelThreads) void sq_select(Dims dm, const float* __restrict__ cosv,
+                                                        int32_t* __restrict__ q_idx, int n_keep) {
+  constexpr int NW = kSelThreads / 64;
+  __shared__ RadixSelectLds rs;
+  __shared__ uint32_t wsum[NW + 1];
+  __shared__ uint32_t sel_key[kMaxKeep];
+  __shared__ uint32_t sel_idx[kMaxKeep];
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int C = dm.C;
+  const float* cv = cosv + (size_t)(b * dm.n_q + h) * C;
+  const int lo = threadIdx.x * IPT;
+  uint32_t key[IPT];
+  uint32_t valid = 0u;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    const bool in = lo + j < C;
+    key[j] = in ? okey(cv[lo + j]) : 0xFFFFFFFFu;
+    valid |= (in ? 1u : 0u) << j;
+  }
+  select_lowest_ranked<IPT>(key, valid, lo, n_keep, rs, wsum, sel_key, sel_idx,
+                            q_idx + (size_t)(b * dm.n_q + h) * n_keep);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Mean, cosines and selection of one (b, q-head) in one block, for chunks short enough that the block can hold the
+// head's queries in registers: every row is requested at once (one memory latency; a compute unit that fetches a
+// few rows per thread at a time pulls only a few tens of GB/s) and read only once.
+// Column sums are formed per group of concurrently handled rows and the groups added in a fixed order, so the mean is
+// bit-reproducible here too (its rounding differs from the tiled kernels' in the last bits: the two routes are
+// never mixed within one call).
+template <typename T>
+struct Raw8;   // eight consecutive elements as loaded
+template <>
+struct Raw8<uint16_t> {
+  u32x4 r;
+  __device__ __forceinline__ void load(const uint16_t* p) { r = *reinterpret_cast<const u32x4*>(p); }
+  __device__ __forceinline__ void widen(float (&v)[8]) const {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(r[i] << 16);
+      v[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
+    }
+  }
+};
+template <>
+struct Raw8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float* p) {
+    a = *reinterpret_cast<const float4*>(p);
+    b = *reinterpret_cast<const float4*>(p + 4);
+  }
+  __device__ __forceinline__ void widen(float (&v)[8]) const {
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+};
+
+template <typename T, int D, int NR>   // NR: rows per thread (all held in registers)
+__global__ __launch_bounds__(kSelThreads) void sq_head_select(Dims dm, const T* __restrict__ q,
+                                                             int32_t* __restrict__ q_idx, int n_keep) {
+  constexpr int CG = D / 8;                  // lanes per row (8 elements each)
+  constexpr int RPB = kSelThreads / CG;      // rows handled concurrently
+  constexpr int IPT = (RPB * NR + kSelThreads - 1) / kSelThreads;   // cosines per thread in the selection
+  constexpr int NW = kSelThreads / 64;
+  __shared__ RadixSelectLds rs;
+  __shared__ uint32_t wsum[NW + 1];
+  __shared__ uint32_t sel_key[kMaxKeep];
+  __shared__ uint32_t sel_idx[kMaxKeep];
+  __shared__ float mean[D];
+  __shared__ float mnorm;
+  __shared__ float buf[RPB * D];             // column partials, then the cosines (RPB * NR <= RPB * D of them)
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int C = dm.C;
+  const int tid = threadIdx.x;
+  const int cg = tid % CG, rr = tid / CG;
+  const T* base = q + b * dm.qs[0] + h * dm.qs[1];
+  Raw8<T> rows[NR];
+#pragma unroll
+  for (int u = 0; u < NR; ++u) rows[u].load(base + (size_t)min(u * RPB + rr, C - 1) * dm.qs[2] + cg * 8);
+  // ---- column sums, mean, its norm ----
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int u = 0; u < NR; ++u) {
+    float v[8];
+    rows[u].widen(v);
+    if (u * RPB + rr < C) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += v[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) buf[rr * D + cg * 8 + e] = acc[e];
+  __syncthreads();
+  if (tid < D) {
+    float s = 0.f;
+    for (int i = 0; i < RPB; ++i) s += buf[i * D + tid];
+    mean[tid] = s / (float)C;
+  }
+  __syncthreads();
+  if (tid < 64) {   // one wave: squared norm of the mean
+    float ss = 0.f;
+    for (int i = tid; i < D; i += 64) ss += mean[i] * mean[i];
+    ss = wave64_sum(ss);
+    if (tid == 0) mnorm = fmaxf(sqrtf(ss), kNormEps);
+  }
+  __syncthreads();   // (also: the partials in buf are dead from here on)
+  float m[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) m[e] = mean[cg * 8 + e];
+  const float mn = mnorm;
+  // ---- cosines of the rows held in registers ----
+#pragma unroll
+  for (int u = 0; u < NR; ++u) {
+    float v[8];
+    rows[u].widen(v);
+    float dot = 0.f, qq = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      dot += v[e] * m[e];
+      qq += v[e] * v[e];
+    }
+    if constexpr (CG == 16) {
+      dot = row16_sum(dot);
+      qq = row16_sum(qq);
+    } else {
+      dot = group_sum<CG>(dot);
+      qq = group_sum<CG>(qq);
+    }
+    const int tok = u * RPB + rr;
+    if (cg == 0 && tok < C) buf[tok] = dot / (fmaxf(sqrtf(qq), kNormEps) * mn) + 0.0f;
+  }
+  __syncthreads();
+  const int lo = tid * IPT;
+  uint32_t key[IPT];
+  uint32_t valid = 0u;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    const bool in = lo + j < C;
+    key[j] = in ? okey(buf[in ? lo + j : 0]) : 0xFFFFFFFFu;
+    valid |= (in ? 1u : 0u) << j;
+  }
+  select_lowest_ranked<IPT>(key, valid, lo, n_keep, rs, wsum, sel_key, sel_idx,
+                            q_idx + (size_t)(b * dm.n_q + h) * n_keep);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -265,20 +399,30 @@ static hipError_t launch_typed(const Dims& dm, const void* q, int32_t* q_idx, fl
   } else if (dm.flags & QUOKA_SELECT_UNIFORM) {
     hipLaunchKernelGGL((sq_qbar<T, D, kUniform>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep, zero, zero_words);
   } else {
-    const int n_tiles = (dm.C + kSqTile - 1) / kSqTile;
-    dim3 grid(n_tiles, dm.n_q, dm.b);
-    hipLaunchKernelGGL((sq_partial_sums<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, n_tiles);
-    hipLaunchKernelGGL((sq_cosine<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, ws_cos, n_tiles);
     const dim3 sgrid(dm.n_q, dm.b), sblock(kSelThreads);
     const int ipt = (dm.C + kSelThreads - 1) / kSelThreads;
-    if (ipt <= 1) {
-      hipLaunchKernelGGL((sq_select<1>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
-    } else if (ipt <= 2) {
-      hipLaunchKernelGGL((sq_select<2>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
-    } else if (ipt <= 4) {
-      hipLaunchKernelGGL((sq_select<4>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+    // One block per head for everything when the block can hold the head's queries in registers (8 rows of 8 elements
+    // per thread) AND the heads alone give half the compute units a block (batches).  Measured: 256 heads of 512 tokens
+    // 14.8 us against 24 us for the three launches below; with only 32 heads (1024 tokens each) one compute unit per
+    // head is the slower way (20.7 against 16.5 us), so single sequences spread the two reads of Q over the whole chip.
+    constexpr int kRowsPerThread = 8;
+    constexpr int kRowsAtOnce = kSelThreads / (D / 8);
+    if (dm.C <= kRowsAtOnce * kRowsPerThread && dm.b * dm.n_q >= 128) {
+      hipLaunchKernelGGL((sq_head_select<T, D, kRowsPerThread>), sgrid, sblock, 0, st, dm, qp, q_idx, n_keep);
     } else {
-      hipLaunchKernelGGL((sq_select<8>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+      const int n_tiles = (dm.C + kSqTile - 1) / kSqTile;
+      dim3 grid(n_tiles, dm.n_q, dm.b);
+      hipLaunchKernelGGL((sq_partial_sums<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, n_tiles);
+      hipLaunchKernelGGL((sq_cosine<T, D>), grid, dim3(kSqThreads), 0, st, dm, qp, ws_part, ws_cos, n_tiles);
+      if (ipt <= 1) {
+        hipLaunchKernelGGL((sq_select<1>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+      } else if (ipt <= 2) {
+        hipLaunchKernelGGL((sq_select<2>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+      } else if (ipt <= 4) {
+        hipLaunchKernelGGL((sq_select<4>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+      } else {
+        hipLaunchKernelGGL((sq_select<8>), sgrid, sblock, 0, st, dm, ws_cos, q_idx, n_keep);
+      }
     }
     hipLaunchKernelGGL((sq_qbar<T, D, kFromIndex>), qgrid, dim3(64), 0, st, dm, qp, q_idx, qbar, n_keep, zero, zero_words);
   }

@@ -41,6 +41,10 @@ SELECT_CASES = [
     dict(dtype="bf16", n_q=2, n_kv=1, d=128, chunk=8192, n_retain=128),                 # largest chunk, largest N_Q
     dict(dtype="bf16", n_q=2, n_kv=2, d=128, chunk=5000, n_retain=1),                   # a single retained query
     dict(dtype="bf16", n_q=2, n_kv=2, d=128, chunk=700, n_retain=3),
+    # batches of short chunks (at least 128 heads): mean, cosines and selection of a head in one block
+    dict(dtype="bf16", n_q=32, n_kv=8, d=64, chunk=200, n_retain=48, batch=4),
+    dict(dtype="f32", n_q=64, n_kv=16, d=128, chunk=300, n_retain=17, batch=2),
+    dict(dtype="bf16", n_q=32, n_kv=4, d=128, chunk=512, n_retain=128, batch=4),
 ]
 
 
