@@ -317,10 +317,11 @@ def _probes(torch, pk, dev):
     dst = torch.empty_like(src)
     blocks, iters = 1024, 20000
     pk.quoka_probe_mfma(blocks, 200, sink)
+    pk.quoka_probe_attn_mix(256, 20, sink)
     pk.quoka_probe_read(src, src.numel() * 4, sink)
     dst.copy_(src)
     torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
     ev[0].record()
     pk.quoka_probe_mfma(blocks, iters, sink)
     ev[1].record()
@@ -330,13 +331,18 @@ def _probes(torch, pk, dev):
     for _ in range(5):
         dst.copy_(src)
     ev[3].record()
+    mix_steps = 2000
+    pk.quoka_probe_attn_mix(256, mix_steps, sink)
+    ev[4].record()
     torch.cuda.synchronize()
+    mix = 256 * 8 * mix_steps * 32 * 32768 / (ev[3].elapsed_time(ev[4]) * 1e-3) / 1e12
     mfma = blocks * 4 * iters * 4 * 32768 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e12
     read = 5 * src.numel() * 4 / (ev[1].elapsed_time(ev[2]) * 1e-3) / 1e9
     copy = 5 * 2 * src.numel() * 4 / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9
-    return {"mfma_loop_tflops": mfma, "stream_read_gbs": read, "device_copy_gbs": copy,
-            "what": "register-only v_mfma_f32_32x32x16_bf16 loop (2 waves per SIMD); one coalesced read of 1 GiB; "
-                    "device copy of 1 GiB counted as read + write"}
+    return {"mfma_loop_tflops": mfma, "attn_mix_tflops": mix, "stream_read_gbs": read, "device_copy_gbs": copy,
+            "what": "register-only v_mfma_f32_32x32x16_bf16 loop (2 waves per SIMD); the attention step's instruction "
+                    "mix (32 MFMAs + 32 exponentials + ~160 vector ops per wave and step, 2 waves per SIMD, no memory "
+                    "side); one coalesced read of 1 GiB; device copy of 1 GiB counted as read + write"}
 
 
 def main():
@@ -400,7 +406,9 @@ def main():
                     "traffic": traffic, "traffic_from_profile": traffic_file,
                     "algorithmic_bytes": alg["sparse_bytes"], "algorithmic_flops": alg["sparse_flops"],
                     "kernel_us": attn_us, "achievable_peak": probes["mfma_loop_tflops"],
-                    "frac_of_achievable": attn_tflops / probes["mfma_loop_tflops"]}
+                    "frac_of_achievable": attn_tflops / probes["mfma_loop_tflops"],
+                    "instruction_mix_ceiling": probes["attn_mix_tflops"],
+                    "frac_of_mix_ceiling": attn_tflops / probes["attn_mix_tflops"]}
     else:
         roofline = {"kernel": "attn_f32 (quoka_sparse_attn)", "bound": "alu", "achieved": attn_tflops,
                     "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / FP32_VALU_PEAK_TFLOPS,

@@ -210,7 +210,11 @@ quoka_status quoka_topk_keys_noalloc(const quoka_shape* shape, const float* scor
  *   quoka_probe_mfma  `blocks` blocks of 4 waves, each wave issuing 4 * iters register-only
  *                     v_mfma_f32_32x32x16_bf16 (32768 flop each); sink: device float, never written in practice.
  *   quoka_probe_read  reads `bytes` (multiple of 16; src 16-byte aligned, device memory) once with coalesced
- *                     16-byte loads and writes nothing.                                                         */
+ *                     16-byte loads and writes nothing.
+ *   quoka_probe_attn_mix  `blocks` blocks of 8 waves, each wave running `steps` steps of the bf16 attention kernel's
+ *                     instruction mix without its memory side: 32 MFMAs (32768 flop each), 32 exponentials and about
+ *                     160 plain vector operations per step.  Its rate is the ceiling of that work split.        */
+quoka_status quoka_probe_attn_mix(int blocks, int steps, float* sink, void* stream);
 quoka_status quoka_probe_mfma(int blocks, int iters, float* sink, void* stream);
 quoka_status quoka_probe_read(const void* src, size_t bytes, float* sink, void* stream);
 

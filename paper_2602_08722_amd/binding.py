@@ -22,7 +22,7 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTS = (
     "quoka_workspace_bytes", "quoka_select_queries", "quoka_score_keys", "quoka_topk_keys", "quoka_select_keys",
     "quoka_sparse_attn", "quoka_dense_attn", "quoka_chunk_attn", "quoka_prefill_attn", "quoka_topk_keys_noalloc",
-    "quoka_probe_mfma", "quoka_probe_read", "quoka_status_string", "quoka_version",
+    "quoka_probe_mfma", "quoka_probe_read", "quoka_probe_attn_mix", "quoka_status_string", "quoka_version",
 )
 _STATUS_EXPORTS = EXPORTS[:-2]   # everything that returns a quoka_status
 
@@ -75,6 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.quoka_topk_keys_noalloc.argtypes = [SH, F32P, I32P, I32P, I32P, I32P, P]
     lib.quoka_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, F32P, P]
     lib.quoka_probe_read.argtypes = [P, SZ, F32P, P]
+    lib.quoka_probe_attn_mix.argtypes = [ctypes.c_int, ctypes.c_int, F32P, P]
     for name in _STATUS_EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     lib.quoka_status_string.argtypes = [ctypes.c_int]
@@ -172,6 +173,11 @@ def quoka_topk_keys_noalloc(shape, scores, kv_lens, budgets, k_idx, k_cnt, strea
 
 def quoka_probe_mfma(blocks: int, iters: int, sink, stream=None) -> None:
     _check("quoka_probe_mfma", load_library().quoka_probe_mfma(int(blocks), int(iters), _ptr(sink), _stream(stream)))
+
+
+def quoka_probe_attn_mix(blocks: int, steps: int, sink, stream=None) -> None:
+    _check("quoka_probe_attn_mix", load_library().quoka_probe_attn_mix(int(blocks), int(steps), _ptr(sink),
+                                                                       _stream(stream)))
 
 
 def quoka_probe_read(src, nbytes: int, sink, stream=None) -> None:

@@ -361,6 +361,11 @@ quoka_status quoka_probe_mfma(int blocks, int iters, float* sink, void* stream) 
   return from_hip(quoka::launch_probe_mfma(blocks, iters, sink, static_cast<hipStream_t>(stream)));
 }
 
+quoka_status quoka_probe_attn_mix(int blocks, int steps, float* sink, void* stream) {
+  if (blocks < 1 || blocks > 65535 || steps < 1 || sink == nullptr) return QUOKA_EINVAL;
+  return from_hip(quoka::launch_probe_attn_mix(blocks, steps, sink, static_cast<hipStream_t>(stream)));
+}
+
 quoka_status quoka_probe_read(const void* src, size_t bytes, float* sink, void* stream) {
   if (src == nullptr || sink == nullptr || bytes == 0 || bytes % 16 != 0 || !aligned16(src)) return QUOKA_EINVAL;
   return from_hip(quoka::launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream)));

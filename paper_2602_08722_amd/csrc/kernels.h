@@ -75,6 +75,7 @@ hipError_t launch_attn_f32(const Dims& dm, const AttnArgs& a, hipStream_t st);
 
 // --- measurement aids (probes.hip) ------------------------------------------------------------------
 hipError_t launch_probe_mfma(int blocks, int iters, float* sink, hipStream_t st);
+hipError_t launch_probe_attn_mix(int blocks, int steps, float* sink, hipStream_t st);
 hipError_t launch_probe_read(const void* src, size_t bytes, float* sink, hipStream_t st);
 
 }  // namespace quoka
