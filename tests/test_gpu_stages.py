@@ -441,6 +441,24 @@ def test_scoring_topk_and_attention_at_the_longest_cache(d):
     assert not np.isnan(sc).any()
     want_idx = O.topk_keys(sc.astype(np.float64), B)
     assert np.array_equal(buf.k_idx[0, :, :B].cpu().numpy(), want_idx)
+    # the one-stage selection (provisional scores, exact re-scoring near the cut) must give the same list bit for bit;
+    # at this length a scoring block works through more than 255 steps of one head (its 16-bit histogram counters are
+    # flushed on the way) and the candidate list runs to thousands of entries over 8192 tiles
+    staged_idx = buf.k_idx.clone()
+    buf.k_idx.fill_(-1)
+    buf.scores.fill_(float("nan"))
+    buf.select_keys()
+    torch.cuda.synchronize()
+    assert int(buf.k_cnt[0, 0]) == B
+    assert torch.equal(buf.k_idx[0, :, :B], staged_idx[0, :, :B])
+    got2 = buf.scores[0, :, pos_t].cpu().numpy()
+    qb32 = gen.from_torch(buf.qbar)[0, 0]
+    delta = qb32.astype(np.float64) - gen.workloads.bf16_round(qb32).astype(np.float64)
+    assert np.abs(got2 - want).max() <= float(np.sqrt((delta * delta).sum(axis=1)).max()) + 4e-6
+    cut = np.sort(sc[0])[T - B]
+    near = np.abs(want[0] - cut) <= 2.0 ** -11 - 1e-5
+    if near.any():
+        assert np.abs(got2[0][near] - want[0][near]).max() <= P.TOL_SCORE
     # attention over rows gathered from all over the cache: the oracle gets the gathered rows as its whole cache
     buf.out.fill_(float("nan"))
     buf.sparse_attn()
