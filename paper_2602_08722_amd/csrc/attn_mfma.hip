@@ -180,8 +180,7 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
       if (cache_ && sparse) {                                                                      \
         _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                                          \
           const uint32_t n_ = (uint32_t)min(base_ + r0 + RPI * i, last_); /* tail slots repeat a real row */ \
-          /* clamped to the cache extent: a malformed list (negative or too large) cannot leave the tensor */ \
-          rows[i] = min(*reinterpret_cast<const uint32_t*>(kidx + n_ * 4u), idx_max);               \
+          rows[i] = *reinterpret_cast<const uint32_t*>(kidx + n_ * 4u); /* clamped where it is used */ \
         }                                                                                          \
       } else {                                                                                     \
         _Pragma("unroll") for (int i = 0; i < NLD; ++i)                                            \
@@ -194,8 +193,12 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     const bool cache_ = (IT) >= n_cht;                                                             \
     const char* tb_ = cache_ ? cache_base : chunk_base;                                            \
     const uint32_t rb_ = cache_ ? cache_row_bytes : chunk_row_bytes;                               \
+    /* Cache rows are clamped to the cache extent: a malformed list (negative or too large) cannot leave the tensor. \
+       The clamp sits here, not where the index is fetched: there it would make every wave wait for the fetch it \
+       has just issued. */                                                                          \
+    const uint32_t row_max_ = cache_ ? idx_max : 0xffffffffu;                                      \
     _Pragma("unroll") for (int i = 0; i < NLD; ++i)                                                \
-      R[i] = *reinterpret_cast<const u32x4*>(tb_ + (rows[i] * rb_ + (uint32_t)cg * 16u));          \
+      R[i] = *reinterpret_cast<const u32x4*>(tb_ + (min(rows[i], row_max_) * rb_ + (uint32_t)cg * 16u)); \
   } while (0)
 
   // tile 0 is the first chunk tile (the chunk is never empty): no index, no cache length
@@ -323,24 +326,36 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     l_run += psum;
   };
 
-  // Both sets run the same program -- per tile: stage, barrier, issue, S = K Q^T, barrier, softmax and P V -- but set 1
-  // enters it one barrier late (and set 0 leaves it one barrier late), so the k-th barrier of set 0 is the (k-1)-th of
-  // set 1 and the sets stay half a step apart: while one forms S the other runs softmax and P V.
-  // Visibility: K of tile j is stored by set 0 before block barrier 2j and first read after it; V of tile j is stored
-  // by set 1 before block barrier 2j+1 (its own first barrier of the step) and first read, by set 0, after it.
-  // Reuse: a stage is overwritten two steps later, by the set that stored it, after that set's own last read; the
-  // other set's last read of it lies at least one block barrier earlier.
-  if (set == 1) __builtin_amdgcn_s_barrier();
-  for (int j = 0; j < n_tiles; ++j) {
-    {   // this set's tensor (K or V) of tile j: registers -> LDS
-      uint16_t* dst = reinterpret_cast<uint16_t*>(smem + (size_t)(j & 1) * Cfg::kStageBytes + stage_off_mine);
+  // Both sets run the same program -- per tile: barrier, stage the next tile and request the one after, S = K Q^T,
+  // barrier, softmax and P V -- but set 1 enters it one barrier late (and set 0 leaves it one barrier late), so the
+  // k-th barrier of set 0 is the (k-1)-th of set 1 and the sets stay half a step apart: while one forms S the other
+  // runs softmax and P V.  A set writes its tensor (set 0: K, set 1: V) of tile j+1 into LDS right after the first
+  // barrier of its step j, at the start of the half in which it only feeds the matrix core; the half that ends in
+  // softmax and P V, which sets the pace, carries no staging and no wait for global memory.
+  // Visibility: K of tile j+1 is stored by set 0 after block barrier 2j and is complete before block barrier 2j+2 (the
+  // fence of the storing waves' next first barrier), after which it is first read; V of tile j+1 is stored by set 1
+  // after block barrier 2j+1, complete before 2j+3 and first read, by set 0, after 2j+3.
+  // Reuse: the stage written in step j held tile j-1, whose last readers (both sets' S of that tile for K, both sets'
+  // P V for V) finished before the barrier the write follows.
+  auto stage_tile = [&](int t) __attribute__((always_inline)) {   // this set's tensor of tile t: registers -> LDS
+    uint16_t* dst = reinterpret_cast<uint16_t*>(smem + (size_t)(t & 1) * Cfg::kStageBytes + stage_off_mine);
 #pragma unroll
-      for (int i = 0; i < NLD; ++i) *reinterpret_cast<u32x4*>(dst + (r0 + RPI * i) * ld_mine + cg * 8) = R[i];
-    }
+    for (int i = 0; i < NLD; ++i) *reinterpret_cast<u32x4*>(dst + (r0 + RPI * i) * ld_mine + cg * 8) = R[i];
+  };
+  stage_tile(0);
+  if (1 < n_tiles) {
+    QUOKA_ISSUE(1);
+    QUOKA_RESOLVE(2);
+  }
+  if (set == 1) __syncthreads();   // (with the fence: V of tile 0 is complete before set 0 passes its first barrier)
+  for (int j = 0; j < n_tiles; ++j) {
     __syncthreads();
     if (j + 1 < n_tiles) {
-      QUOKA_ISSUE(j + 1);
-      QUOKA_RESOLVE(j + 2);
+      stage_tile(j + 1);
+      if (j + 2 < n_tiles) {
+        QUOKA_ISSUE(j + 2);
+        QUOKA_RESOLVE(j + 3);
+      }
     }
     if (!computes(j)) {   // nothing visible for this wave in its share of the tile
       __builtin_amdgcn_s_barrier();
