@@ -61,8 +61,16 @@ enum {
   QUOKA_SCORE_QBAR_BF16 = 8, /* cheaper Qbar K^T (the direction the paper's conclusion names): Qbar is rounded to
                                 bfloat16 (nearest, ties to even) before the product; scores then differ from the
                                 exact ones by at most 2^-9 * sum_i |qbar_i| (times ||k|| with QUOKA_SCORE_DOT)     */
-  QUOKA_SELECT_UNIFORM = 4 /* uniformly sampled queries (the query-sampling baseline of Sec. 4) instead of the lowest
-                              cosines: positions floor(r * C / N_Q), r = 0..N_Q-1, the same for every head           */
+  QUOKA_SELECT_UNIFORM = 4, /* uniformly sampled queries (the query-sampling baseline of Sec. 4) instead of the lowest
+                               cosines: positions floor(r * C / N_Q), r = 0..N_Q-1, the same for every head          */
+  QUOKA_ATTN_SCALE_F32 = 16 /* attention (quoka_sparse_attn, quoka_dense_attn and the calls built on them), bfloat16
+                               prefill-sized chunks: apply the 1/sqrt(d) of Eq. 2-3 to the float32 products Q K^T.
+                               Without the flag the factor is multiplied into the bfloat16 Q operand, which saves a
+                               vector instruction per score (the kernel is 5 % faster) and rounds Q once more: the
+                               logits then carry a relative error of 2^-9, invisible for unit-variance inputs (output
+                               error 0.001 either way) and growing with the size of the logits -- 0.03 absolute in the
+                               output at four times that size, 0.06 at eight, where the flag keeps it at 0.015.  Other
+                               kernels (float32, decode-sized chunks) always scale in float32                       */
 };
 
 /* Problem description.  Notation of the paper: b, n_Q, n_KV, d, B_CP (chunk_len), T (kv length),

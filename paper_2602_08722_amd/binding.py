@@ -105,7 +105,7 @@ def _strides3(t: torch.Tensor):
     return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
 
 
-QUOKA_SCORE_DOT, QUOKA_SCORE_MEAN, QUOKA_SELECT_UNIFORM, QUOKA_SCORE_QBAR_BF16 = 1, 2, 4, 8   # quoka.h
+QUOKA_SCORE_DOT, QUOKA_SCORE_MEAN, QUOKA_SELECT_UNIFORM, QUOKA_SCORE_QBAR_BF16, QUOKA_ATTN_SCALE_F32 = 1, 2, 4, 8, 16   # quoka.h
 
 
 def make_shape(q: torch.Tensor, k_cache: torch.Tensor, k_chunk: torch.Tensor, out: torch.Tensor,

@@ -31,7 +31,8 @@ struct WsLayout {
 quoka_status check_shape(const quoka_shape* s, Dims* dm) {
   if (s == nullptr) return QUOKA_EINVAL;
   if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->chunk_len < 1 || s->n_retain < 1 ||
-      s->max_kv_len < 0 || s->max_budget < 0 || (s->score_flags & ~(QUOKA_SCORE_DOT | QUOKA_SCORE_MEAN | QUOKA_SELECT_UNIFORM | QUOKA_SCORE_QBAR_BF16)) != 0)
+      s->max_kv_len < 0 || s->max_budget < 0 || (s->score_flags & ~(QUOKA_SCORE_DOT | QUOKA_SCORE_MEAN | QUOKA_SELECT_UNIFORM | QUOKA_SCORE_QBAR_BF16 |
+                          QUOKA_ATTN_SCALE_F32)) != 0)
     return QUOKA_EINVAL;
   if (s->n_q_heads % s->n_kv_heads != 0) return QUOKA_EINVAL;
   if (s->max_budget > s->max_kv_len) return QUOKA_EINVAL;

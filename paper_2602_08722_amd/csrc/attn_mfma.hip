@@ -75,7 +75,13 @@ struct AttnCfg {
   static constexpr size_t kLdsBytes = 2 * kStageBytes;                          // double buffered
 };
 
-template <int D, bool SPLIT>
+// XS (QUOKA_ATTN_SCALE_F32): the softmax scale is applied to the float32 products, one fused multiply-add per score
+// together with the subtraction of the reference point.  Otherwise the factor log2(e)/sqrt(d) is folded into the bf16 Q
+// operand once and the accumulator of K Q^T starts from minus the reference point, so that the matrix core hands back
+// what the exponential takes and no vector instruction is spent on either -- 5 % faster, at the price of rounding Q a
+// second time: an error of the logits of relative size 2^-9, which shows in the output once the logits are several
+// times those of unit-variance inputs (0.03 absolute at four times, 0.06 at eight).
+template <int D, bool SPLIT, bool XS>
 __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArgs a) {
   using Cfg = AttnCfg<D, SPLIT>;
   constexpr int KT = Cfg::KT, KS = Cfg::KS, LD = Cfg::LD, LDV = Cfg::LDV, CG = Cfg::CG, RPI = Cfg::RPI, NLD = Cfg::NLD,
@@ -153,8 +159,10 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     const uint16_t* qrow = qg + b * dm.qs[0] + h * dm.qs[1] + (size_t)tokq * dm.qs[2] + 8 * hf;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
-    // The softmax scale and the change to base 2 go into Q once, so K Q^T arrives in the exponent's own units.
-    const float qscale = 1.4426950408889634f / sqrtf((float)D);
+  }
+  // the softmax scale and the change to base 2
+  const float qscale = 1.4426950408889634f / sqrtf((float)D);
+  if constexpr (!XS) {   // into Q once, so K Q^T arrives in the exponent's own units
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -216,8 +224,8 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     for (int v = 0; v < 16; ++v) o[c][v] = 0.f;
   float m_run = -INFINITY;   // running row max, in the scaled log2 domain
   float l_run = 0.f;         // this half wave's share of the running row sum
-  // -m_use in every entry: the accumulator K Q^T starts from, so the matrix core hands back s - m_use and the
-  // exponential needs no subtraction of its own.  Rewritten only when the reference point moves.
+  // What the accumulator of K Q^T starts from.  !XS: -m_use in every entry, so the matrix core hands back s - m_use
+  // and the exponential needs no subtraction of its own; rewritten only when the reference point moves.  XS: zero.
   f32x16 cinit;
 #pragma unroll
   for (int v = 0; v < 16; ++v) cinit[v] = 0.f;
@@ -270,32 +278,54 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
-    mx = fmaxf(mx, other_half(mx));   // relative to the reference point the tile was formed with
+    mx = fmaxf(mx, other_half(mx));
     constexpr float kLazy = 8.0f;
-    const bool moves = m_run == -INFINITY ? mx > -INFINITY : mx > kLazy;
-    if (__builtin_amdgcn_ballot_w64(moves) != 0) {   // wave-uniform branch
-      const float m_old = (m_run == -INFINITY) ? 0.f : m_run;    // what the tile's scores are relative to
-      const float m_new = moves ? m_old + mx : m_run;
-      const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_fin);
-      const float shift = m_fin - m_old;
-      m_run = m_new;
-      l_run *= alpha;
+    if constexpr (XS) {
+      mx *= qscale;   // the row's largest score of this tile, scaled log2 domain (the products themselves are raw)
+      const bool moves = m_run == -INFINITY ? mx > -INFINITY : mx > m_run + kLazy;
+      if (__builtin_amdgcn_ballot_w64(moves) != 0) {   // wave-uniform branch
+        const float m_new = moves ? mx : m_run;
+        const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_fin);   // 0 for a row without a reference so far, 1 if unmoved
+        m_run = m_new;
+        l_run *= alpha;
 #pragma unroll
-      for (int c = 0; c < DB; ++c)
+        for (int c = 0; c < DB; ++c)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[c][v] *= alpha;
+          for (int v = 0; v < 16; ++v) o[c][v] *= alpha;
+      }
+      const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;   // (a row that has seen nothing yet: all its scores are -inf)
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[nb][v] -= shift;
+        for (int v = 0; v < 16; ++v) s[nb][v] = __builtin_amdgcn_exp2f(fmaf(s[nb][v], qscale, neg_m));
+    } else {
+      // (mx is relative to the reference point the tile was formed with)
+      const bool moves = m_run == -INFINITY ? mx > -INFINITY : mx > kLazy;
+      if (__builtin_amdgcn_ballot_w64(moves) != 0) {   // wave-uniform branch
+        const float m_old = (m_run == -INFINITY) ? 0.f : m_run;    // what the tile's scores are relative to
+        const float m_new = moves ? m_old + mx : m_run;
+        const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_fin);
+        const float shift = m_fin - m_old;
+        m_run = m_new;
+        l_run *= alpha;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) cinit[v] = -m_fin;
+        for (int c = 0; c < DB; ++c)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[c][v] *= alpha;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) s[nb][v] -= shift;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) cinit[v] = -m_fin;
+      }
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[nb][v] = __builtin_amdgcn_exp2f(s[nb][v]);
     }
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s[nb][v] = __builtin_amdgcn_exp2f(s[nb][v]);
     // lane's corner of every transposing read: key 4*hf + (lane%16)/4, dims 16*((lane/16)%2) + 4*(lane%4)
     const tr_ptr vtr = (tr_ptr)(vt + (4 * hf + ((lane & 15) >> 2)) * LDV + 16 * ((lane >> 4) & 1) + 4 * (lane & 3));
     float psum = 0.f;
@@ -417,12 +447,12 @@ __global__ __launch_bounds__(2 * kSetThreads, 2) void attn_bf16(Dims dm, AttnArg
 #undef QUOKA_RESOLVE
 #undef QUOKA_ISSUE
 
-template <int D, bool SPLIT>
-static hipError_t launch_ds(const Dims& dm, const AttnArgs& a, hipStream_t st) {
+template <int D, bool SPLIT, bool XS>
+static hipError_t launch_dsx(const Dims& dm, const AttnArgs& a, hipStream_t st) {
   using Cfg = AttnCfg<D, SPLIT>;
   constexpr size_t lds = Cfg::kLdsBytes;
   static std::atomic<uint64_t> lds_done{0};
-  const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_bf16<D, SPLIT>), lds, lds_done);
+  const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_bf16<D, SPLIT, XS>), lds, lds_done);
   if (e != hipSuccess) return e;
   const int nrb = dm.g * ((dm.C + 31) / 32);
   const int half = (nrb + 1) / 2;
@@ -432,8 +462,14 @@ static hipError_t launch_ds(const Dims& dm, const AttnArgs& a, hipStream_t st) {
   // (measured at 512 blocks, 4096-token chunk over 131072 cached tokens: 3.5 % faster than pairing; a launch of one
   // round needs the pairing, or its last block sets the time alone)
   aa.adjacent = (long long)grid.x * grid.y * grid.z >= 2 * kComputeUnits ? 1 : 0;
-  hipLaunchKernelGGL((attn_bf16<D, SPLIT>), grid, dim3(2 * kSetThreads), lds, st, dm, aa);
+  hipLaunchKernelGGL((attn_bf16<D, SPLIT, XS>), grid, dim3(2 * kSetThreads), lds, st, dm, aa);
   return hipGetLastError();
+}
+
+template <int D, bool SPLIT>
+static hipError_t launch_ds(const Dims& dm, const AttnArgs& a, hipStream_t st) {
+  if (dm.flags & QUOKA_ATTN_SCALE_F32) return launch_dsx<D, SPLIT, true>(dm, a, st);
+  return launch_dsx<D, SPLIT, false>(dm, a, st);
 }
 
 template <int D>

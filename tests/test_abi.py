@@ -76,7 +76,7 @@ def test_workspace_query_and_status_strings(pk):
     (dict(chunk_len=0), 1),
     (dict(n_retain=0), 1),
     (dict(max_budget=2000), 1),                    # budget extent beyond the cache extent
-    (dict(score_flags=16), 1),
+    (dict(score_flags=32), 1),
     (dict(head_dim=96), 2),
     (dict(dtype=7), 2),
     (dict(n_retain=129), 2),
@@ -155,11 +155,11 @@ def test_flag_and_enum_values_match_the_header(pk):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     vals = {m.group(1): int(m.group(2)) for m in re.finditer(r"\b(QUOKA_[A-Z0-9_]+)\s*=\s*(\d+)", text)}
     for name in ("QUOKA_F32", "QUOKA_BF16", "QUOKA_SCORE_DOT", "QUOKA_SCORE_MEAN", "QUOKA_SELECT_UNIFORM",
-                 "QUOKA_SCORE_QBAR_BF16"):
+                 "QUOKA_SCORE_QBAR_BF16", "QUOKA_ATTN_SCALE_F32"):
         assert name in vals, name
         assert getattr(pk, name) == vals[name], name
-    flags = [v for k, v in vals.items() if k.startswith(("QUOKA_SCORE_", "QUOKA_SELECT_"))]
-    assert sorted(flags) == [1, 2, 4, 8]           # distinct single bits
+    flags = [v for k, v in vals.items() if k.startswith(("QUOKA_SCORE_", "QUOKA_SELECT_", "QUOKA_ATTN_"))]
+    assert sorted(flags) == [1, 2, 4, 8, 16]       # distinct single bits
     # every flag bit is accepted, the next bit is not
-    assert _ws_status(pk, _shape(pk, score_flags=15))[0] == 0
-    assert _ws_status(pk, _shape(pk, score_flags=16))[0] == 1
+    assert _ws_status(pk, _shape(pk, score_flags=31))[0] == 0
+    assert _ws_status(pk, _shape(pk, score_flags=32))[0] == 1

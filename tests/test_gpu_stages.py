@@ -19,11 +19,12 @@ def _pk():
     return pk
 
 
-def _buffers(w, max_budget=None):
+def _buffers(w, max_budget=None, score_flags=0):
     pk = _pk()
     t = gen.to_torch(w, "cuda:0")
     mb = max_budget if max_budget is not None else min(max(w.budgets), w.t_max)
-    buf = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain, max_budget=mb)
+    buf = pk.ChunkBuffers(t["q"], t["k"], t["v"], t["kc"], t["vc"], w.kv_lens, w.budgets, w.n_retain, max_budget=mb,
+                          score_flags=score_flags)
     return buf
 
 
@@ -346,13 +347,21 @@ ATTN_CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", ATTN_CASES,
-                         ids=lambda c: "-".join(f"{k}{v}" if len(str(v)) < 40 else f"{k}[{len(v)} values]" for k, v in c.items()))
-def test_sparse_and_dense_attention(case):
+def _attn_id(c):
+    return "-".join(f"{k}{v}" if len(str(v)) < 40 else f"{k}[{len(v)} values]" for k, v in c.items())
+
+
+# every case as it is, and the bf16 ones again with the softmax scale applied in float32
+ATTN_PARAMS = [pytest.param(c, False, id=_attn_id(c)) for c in ATTN_CASES] + \
+              [pytest.param(c, True, id=_attn_id(c) + "-scale-f32") for c in ATTN_CASES if c["dtype"] == "bf16"]
+
+
+@pytest.mark.parametrize("case,scale_f32", ATTN_PARAMS)
+def test_sparse_and_dense_attention(case, scale_f32):
     case = dict(case)
     batch = case.pop("batch", 1)
     w = gen.make_custom(batch=batch, n_retain=8, seed=14, **case)
-    buf = _buffers(w)
+    buf = _buffers(w, score_flags=_pk().QUOKA_ATTN_SCALE_F32 if scale_f32 else 0)
     tol = P.TOL_OUT[w.dtype]
     # sparse: feed the oracle's index sets
     k_idx_o = []
@@ -386,6 +395,47 @@ def test_sparse_and_dense_attention(case):
         T = w.kv_lens[b]
         want = O.dense_attn(w.Q[b], w.K[b][:, :T], w.V[b][:, :T], w.Kc[b], w.Vc[b])
         assert P.max_abs(out[b], want) <= tol, f"dense b{b}: {P.max_abs(out[b], want)}"
+
+
+@pytest.mark.parametrize("order", ["growing", "shrinking"])
+@pytest.mark.parametrize("chunk,kv_len", [(160, 1500), (1024, 300), (8, 1500)],
+                         ids=["prefill-kernel", "prefill-kernel-key-split", "decode-kernel"])
+def test_attention_with_logits_that_span_many_octaves(order, chunk, kv_len):
+    """Keys scaled by powers of two along the cache (exact in bf16), up to eight times the size of unit-variance inputs,
+    so that the largest logit keeps growing from tile to tile (the reference point of the online softmax moves again
+    and again, with accumulator rescaling each time) or is met first and everything after it underflows against it.
+    Random N(0,1) inputs never do either.  With QUOKA_ATTN_SCALE_F32 the usual bar holds at this size too; without it
+    the bf16 prefill kernel rounds Q a second time and the documented, looser bound applies."""
+    pk = _pk()
+    w = gen.make_custom(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=chunk, kv_lens=[kv_len], budgets=[kv_len // 3],
+                        n_retain=8, seed=16)
+    T = kv_len
+    octave = (np.arange(T) * 4 // T).astype(np.float64)               # 0 .. 3
+    if order == "shrinking":
+        octave = octave[::-1].copy()
+    w.K[0][:, :T] *= np.exp2(octave)[None, :, None]
+    w.Kc[0] *= 2.0                                                     # the chunk's own keys sit in the middle of the range
+    _, _, ki = O.quoka_select(w.Q[0], w.K[0], w.n_retain, w.budgets[0])
+    want_s, want_lse = O.sparse_attn(w.Q[0], w.K[0], w.V[0], ki, w.Kc[0], w.Vc[0], True)
+    want_d = O.dense_attn(w.Q[0], w.K[0], w.V[0], w.Kc[0], w.Vc[0])
+    for flags, tol in ((pk.QUOKA_ATTN_SCALE_F32, P.TOL_OUT["bf16"]), (0, 8e-2)):
+        buf = _buffers(w, score_flags=flags)
+        idx_host = np.zeros((1, w.n_kv, buf.shape.max_budget), dtype=np.int32)
+        idx_host[0, :, :ki.shape[1]] = ki
+        buf.k_idx.copy_(torch.from_numpy(idx_host))
+        buf.k_cnt.fill_(ki.shape[1])
+        buf.out.fill_(float("nan"))
+        buf.lse.fill_(float("nan"))
+        buf.sparse_attn()
+        torch.cuda.synchronize()
+        assert P.max_abs(gen.from_torch(buf.out)[0], want_s) <= tol, (flags, P.max_abs(gen.from_torch(buf.out)[0], want_s))
+        # log-sum-exp values reach into the tens here: relative bar
+        lse = gen.from_torch(buf.lse)[0]
+        assert np.max(np.abs(lse - want_lse) / (1.0 + np.abs(want_lse))) <= 2e-2
+        buf.out.fill_(float("nan"))
+        buf.dense_attn()
+        torch.cuda.synchronize()
+        assert P.max_abs(gen.from_torch(buf.out)[0], want_d) <= tol, (flags, P.max_abs(gen.from_torch(buf.out)[0], want_d))
 
 
 def test_sparse_attention_accepts_unsorted_indices_and_strided_views():
