@@ -69,6 +69,54 @@ def test_select_queries(case):
         assert P.max_abs(qbar[b], want) <= P.TOL_QBAR
 
 
+@pytest.mark.parametrize("case", [
+    dict(n_q=4, n_kv=2, d=128, chunk=300, n_retain=64),                      # one block per head
+    dict(n_q=4, n_kv=2, d=128, chunk=2600, n_retain=100),                    # several blocks per head
+    dict(n_q=32, n_kv=8, d=64, chunk=256, n_retain=48, batch=4),             # batched: one block does a whole head
+], ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_select_queries_with_repeated_zero_and_rescaled_rows(case):
+    """Rows of the chunk repeated many times (equal cosines bit for bit: the lower position must win wherever the cut
+    falls inside such a group), rows scaled by powers of two from 2^-6 to 2^6 (the cosine of a row does not depend on
+    its length, the mean query does) and zero rows (cosine 0 by definition).  N(0,1) inputs have none of these."""
+    case = dict(case)
+    batch = case.pop("batch", 1)
+    w = gen.make_custom(dtype="bf16", batch=batch, kv_lens=[64] * batch, budgets=[8] * batch, seed=18, **case)
+    rng = np.random.default_rng(7)
+    C = w.chunk
+    groups = []
+    for b in range(w.batch):
+        w.Q[b] *= np.exp2(rng.integers(-6, 7, size=(w.n_q, C)).astype(np.float64))[:, :, None]
+        src = rng.choice(C, size=3, replace=False)
+        members = [np.sort(rng.choice(C, size=max(w.n_retain // 2, 2), replace=False)) for _ in src]
+        for s0, m in zip(src, members):
+            w.Q[b][:, m] = w.Q[b][:, s0:s0 + 1]
+        w.Q[b][:, rng.choice(C, size=5, replace=False)] = 0.0
+        # groups of identical rows as they ended up (later writes may have overwritten earlier ones), per head
+        per_head = []
+        for h in range(w.n_q):
+            seen = {}
+            for i in range(C):
+                seen.setdefault(w.Q[b][h, i].tobytes(), []).append(i)
+            per_head.append([g for g in seen.values() if len(g) > 1])
+        groups.append(per_head)
+    buf = _buffers(w)
+    buf.select_queries()
+    torch.cuda.synchronize()
+    q_idx = gen.from_torch(buf.q_idx)
+    qbar = gen.from_torch(buf.qbar)
+    n_keep = min(w.n_retain, C)
+    for b in range(w.batch):
+        cos = O.cos_to_mean(w.Q[b])
+        for h in range(w.n_q):
+            P.check_query_ranking(q_idx[b, h], cos[h], n_keep, what=f"b{b} h{h}")
+            chosen = set(int(i) for i in q_idx[b, h, :n_keep])
+            for g in groups[b][h]:
+                picked = [i in chosen for i in g]
+                assert picked == sorted(picked, reverse=True), f"b{b} h{h}: a later copy was preferred to an earlier one"
+        want = O.group_mean_queries(w.Q[b], q_idx[b], w.n_kv)
+        assert P.max_abs(qbar[b], want) <= P.TOL_QBAR * max(1.0, float(np.abs(want).max()))
+
+
 SCORE_CASES = [
     dict(dtype="f32", n_q=2, n_kv=1, d=64, chunk=128, n_retain=16, kv_lens=[1000]),
     dict(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=256, n_retain=64, kv_lens=[1500]),          # ragged tail tile
@@ -104,6 +152,43 @@ def test_score_keys(case):
         assert not np.isnan(got).any()
         worst = max(worst, P.max_abs(got, want))
     assert worst <= P.TOL_SCORE, f"max |score - oracle| = {worst}"
+
+
+@pytest.mark.parametrize("kv_len", [3000, 40000], ids=["exact-scorer", "two-pass-stage"])
+def test_scores_with_zero_keys_and_keys_of_very_different_norms(kv_len):
+    """Cosine scores do not depend on the length of a key (Sec. 3.2) and a zero key scores zero: keys scaled by powers
+    of two from 2^-6 to 2^6 (exact in bf16), some keys and one retained query set to zero.  N(0,1) inputs have norms
+    within a few per cent of each other and never a zero."""
+    pk = _pk()
+    w = gen.make_custom(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=96, n_retain=32, kv_lens=[kv_len],
+                        budgets=[kv_len // 8], seed=17)
+    T = kv_len
+    rng = np.random.default_rng(5)
+    w.K[0][:, :T] *= np.exp2(rng.integers(-6, 7, size=(w.n_kv, T)).astype(np.float64))[:, :, None]
+    zero_at = rng.choice(T, size=40, replace=False)
+    w.K[0][:, zero_at] = 0.0
+    w.Q[0][3, 11] = 0.0                       # a zero query: cosine 0 to the mean, neither smallest nor largest
+    buf = _buffers(w)
+    buf.select_queries()
+    buf.scores.fill_(float("nan"))
+    buf.k_idx.fill_(-1)
+    buf.select_keys()
+    torch.cuda.synchronize()
+    q_idx = gen.from_torch(buf.q_idx)
+    qbar = gen.from_torch(buf.qbar)
+    sc = gen.from_torch(buf.scores)[0, :, :T]
+    idx = gen.from_torch(buf.k_idx)[0]
+    n = int(gen.from_torch(buf.k_cnt)[0, 0])
+    assert n == w.budgets[0]
+    want = O.key_scores(w.Q[0], q_idx[0], w.K[0][:, :T], w.n_kv)
+    assert not np.isnan(sc).any()
+    assert np.all(sc[:, zero_at] == 0.0) and np.all(want[:, zero_at] == 0.0)
+    for kv in range(w.n_kv):
+        if P.two_pass_scores(w):
+            P.check_two_pass_scores(sc[kv], want[kv], qbar[0, kv], w.budgets[0], what=f"kv{kv}")
+        else:
+            assert P.max_abs(sc[kv], want[kv]) <= P.TOL_SCORE
+        P.check_topk_set(idx[kv, :n], want[kv], w.budgets[0], what=f"kv{kv}")
 
 
 ABLATION_CASES = [
