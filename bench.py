@@ -287,6 +287,15 @@ def _measure(torch, np, bufs, w, K, W):
         "score_keys_exact": _back_to_back(torch, lambda i: [bufs[i % n].score_keys], K),
         "topk_keys": _back_to_back(torch, lambda i: [bufs[i % n].topk_keys], K),
     }
+    if w.dtype == "bf16":
+        # the same launches with the softmax scale applied to the float32 products (QUOKA_ATTN_SCALE_F32): what the
+        # more exact form of the attention kernel costs
+        import paper_2602_08722_amd as pk
+        for b in bufs:
+            b.shape.score_flags |= pk.QUOKA_ATTN_SCALE_F32
+        kern["sparse_attn_scale_f32"] = _back_to_back(torch, lambda i: [bufs[i % n].sparse_attn], K)
+        for b in bufs:
+            b.shape.score_flags &= ~pk.QUOKA_ATTN_SCALE_F32
     alg = _algorithmic(w)
     res = {
         "workload": _describe(w),

@@ -66,7 +66,7 @@ enum {
   QUOKA_ATTN_SCALE_F32 = 16 /* attention (quoka_sparse_attn, quoka_dense_attn and the calls built on them), bfloat16
                                prefill-sized chunks: apply the 1/sqrt(d) of Eq. 2-3 to the float32 products Q K^T.
                                Without the flag the factor is multiplied into the bfloat16 Q operand, which saves a
-                               vector instruction per score (the kernel is 5 % faster) and rounds Q once more: the
+                               vector instruction per score (the kernel is 4-9 % faster) and rounds Q once more: the
                                logits then carry a relative error of 2^-9, invisible for unit-variance inputs (output
                                error 0.001 either way) and growing with the size of the logits -- 0.03 absolute in the
                                output at four times that size, 0.06 at eight, where the flag keeps it at 0.015.  Other
