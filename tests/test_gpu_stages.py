@@ -486,24 +486,24 @@ def test_sparse_and_dense_attention(case, scale_f32):
 @pytest.mark.parametrize("chunk,kv_len", [(160, 1500), (1024, 300), (8, 1500)],
                          ids=["prefill-kernel", "prefill-kernel-key-split", "decode-kernel"])
 def test_attention_with_logits_that_span_many_octaves(order, chunk, kv_len):
-    """Keys scaled by powers of two along the cache (exact in bf16), up to eight times the size of unit-variance inputs,
-    so that the largest logit keeps growing from tile to tile (the reference point of the online softmax moves again
-    and again, with accumulator rescaling each time) or is met first and everything after it underflows against it.
-    Random N(0,1) inputs never do either.  With QUOKA_ATTN_SCALE_F32 the usual bar holds at this size too; without it
-    the bf16 prefill kernel rounds Q a second time and the documented, looser bound applies."""
+    """Keys scaled by powers of two along the cache (exact in bf16), so that the largest logit keeps growing from tile
+    to tile (the reference point of the online softmax moves again and again, with accumulator rescaling each time) or
+    is met first and everything after it underflows against it.  Random N(0,1) inputs never do either.  With
+    QUOKA_ATTN_SCALE_F32 the usual bar holds up to 32 times the size of unit-variance inputs; without it the bf16
+    prefill kernel rounds Q a second time, and the documented, looser bound is checked at 8 times."""
     pk = _pk()
-    w = gen.make_custom(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=chunk, kv_lens=[kv_len], budgets=[kv_len // 3],
-                        n_retain=8, seed=16)
-    T = kv_len
-    octave = (np.arange(T) * 4 // T).astype(np.float64)               # 0 .. 3
-    if order == "shrinking":
-        octave = octave[::-1].copy()
-    w.K[0][:, :T] *= np.exp2(octave)[None, :, None]
-    w.Kc[0] *= 2.0                                                     # the chunk's own keys sit in the middle of the range
-    _, _, ki = O.quoka_select(w.Q[0], w.K[0], w.n_retain, w.budgets[0])
-    want_s, want_lse = O.sparse_attn(w.Q[0], w.K[0], w.V[0], ki, w.Kc[0], w.Vc[0], True)
-    want_d = O.dense_attn(w.Q[0], w.K[0], w.V[0], w.Kc[0], w.Vc[0])
-    for flags, tol in ((pk.QUOKA_ATTN_SCALE_F32, P.TOL_OUT["bf16"]), (0, 8e-2)):
+    for flags, n_oct, tol in ((pk.QUOKA_ATTN_SCALE_F32, 6, P.TOL_OUT["bf16"]), (0, 4, 8e-2)):
+        w = gen.make_custom(dtype="bf16", n_q=8, n_kv=2, d=128, chunk=chunk, kv_lens=[kv_len], budgets=[kv_len // 3],
+                            n_retain=8, seed=16)
+        T = kv_len
+        octave = (np.arange(T) * n_oct // T).astype(np.float64)        # 0 .. n_oct - 1
+        if order == "shrinking":
+            octave = octave[::-1].copy()
+        w.K[0][:, :T] *= np.exp2(octave)[None, :, None]
+        w.Kc[0] *= 2.0                                                 # the chunk's own keys sit inside the range
+        _, _, ki = O.quoka_select(w.Q[0], w.K[0], w.n_retain, w.budgets[0])
+        want_s, want_lse = O.sparse_attn(w.Q[0], w.K[0], w.V[0], ki, w.Kc[0], w.Vc[0], True)
+        want_d = O.dense_attn(w.Q[0], w.K[0], w.V[0], w.Kc[0], w.Vc[0])
         buf = _buffers(w, score_flags=flags)
         idx_host = np.zeros((1, w.n_kv, buf.shape.max_budget), dtype=np.int32)
         idx_host[0, :, :ki.shape[1]] = ki
@@ -514,7 +514,7 @@ def test_attention_with_logits_that_span_many_octaves(order, chunk, kv_len):
         buf.sparse_attn()
         torch.cuda.synchronize()
         assert P.max_abs(gen.from_torch(buf.out)[0], want_s) <= tol, (flags, P.max_abs(gen.from_torch(buf.out)[0], want_s))
-        # log-sum-exp values reach into the tens here: relative bar
+        # log-sum-exp values reach into the tens and hundreds here: relative bar
         lse = gen.from_torch(buf.lse)[0]
         assert np.max(np.abs(lse - want_lse) / (1.0 + np.abs(want_lse))) <= 2e-2
         buf.out.fill_(float("nan"))
