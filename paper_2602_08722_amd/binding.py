@@ -219,7 +219,7 @@ class PrefillBuffers:
     q [b, n_Q, L, d], k / v [b, n_KV, L, d]; `budget` is B_SA per chunk: an int, or a callable of the cache length.
     """
 
-    def __init__(self, q, k, v, chunk, n_retain, budget):
+    def __init__(self, q, k, v, chunk, n_retain, budget, score_flags=0):
         dev = q.device
         b, n_q, L, d = q.shape
         n_kv = k.shape[1]
@@ -232,7 +232,8 @@ class PrefillBuffers:
         self.budgets_all = torch.tensor(bud, dtype=torch.int32, device=dev)
         self.out = torch.empty_like(q)
         # the shape describes one chunk of `chunk` rows taken from the prompt tensors (their strides, no copies)
-        self.shape = make_shape(q[:, :, :chunk], k, k[:, :, :chunk], self.out[:, :, :chunk], n_retain, max_budget)
+        self.shape = make_shape(q[:, :, :chunk], k, k[:, :, :chunk], self.out[:, :, :chunk], n_retain, max_budget,
+                                score_flags)
         n_keep = self.shape.n_keep
         self.q_idx = torch.empty((b, n_q, n_keep), dtype=torch.int32, device=dev)
         self.qbar = torch.empty((b, n_kv, n_keep, d), dtype=torch.float32, device=dev)
